@@ -1,0 +1,3 @@
+"""fp64 CPU oracle for the attention forward path.  TEST INFRASTRUCTURE ONLY:
+imported by tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg,
+never by the product package."""

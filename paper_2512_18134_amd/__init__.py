@@ -1,0 +1,15 @@
+"""MI355X (gfx950) Flash-Attention forward: the loop of the paper's Section 3
+running example (Fig. 1a / 1f), hand-written in HIP behind a C-ABI library.
+
+`synth` (input generation) imports without the HIP library; everything that
+computes lives in `binding`, which raises at import time if the library has
+not been built (there is no CPU fallback).
+"""
+__all__ = ["synth", "binding"]
+
+
+def __getattr__(name):
+    if name in ("attn_fwd", "attn_strerror", "attn_version", "binding"):
+        from . import binding
+        return binding if name == "binding" else getattr(binding, name)
+    raise AttributeError(name)
