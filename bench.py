@@ -1,0 +1,113 @@
+#!/usr/bin/env python3
+"""Bench: Flash-Attention forward on one MI355X, headline workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+
+A "step" is one attn_fwd call (the whole hot path) over one batch of seeded
+synthetic Q/K/V that is already resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+
+
+def cpu_baseline(cfg, q, k, v, scale, target_seconds=15.0):
+    """Time the fp64 oracle (as it stands) on a bounded sample of rows of the same workload."""
+    from oracle import attn_oracle
+    from paper_2512_18134_amd import synth
+
+    total_rows = cfg["B"] * cfg["H"] * cfg["S_q"]
+    rng = np.random.default_rng(1234)
+    cores = attn_oracle.max_threads()
+
+    def run(n):
+        rows = np.sort(rng.choice(total_rows, size=min(n, total_rows), replace=False)).astype(np.int64)
+        t0 = time.perf_counter()
+        attn_oracle.attn_ref(q, k, v, cfg["causal"], scale, rows=rows)
+        dt = time.perf_counter() - t0
+        i = rows % cfg["S_q"]
+        pairs = np.minimum(i + 1, cfg["S_kv"]).sum() if cfg["causal"] else len(rows) * cfg["S_kv"]
+        return dt, 4.0 * cfg["D"] * float(pairs), len(rows)
+
+    dt, fl, n = run(16 * cores)                      # calibration
+    n2 = int(max(16 * cores, min(total_rows, n * target_seconds / max(dt, 1e-6))))
+    dt, fl, n = run(n2)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d rows (uniform random, seed 1234), %.1f s wall, fp64 two-pass oracle, OpenMP" % (n, total_rows, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="index into the baseline configs (3 = headline D=128 S=16384)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (a single attention kernel; nothing is sharded); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_18134_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg, q, k, v, scale = synth.make_config(args.config)
+    dev = torch.device("cuda:0")
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    o = torch.empty_like(qd)
+    lse = torch.empty(qd.shape[:3], dtype=torch.float32, device=dev)
+    flops = synth.attention_flops(cfg["B"], cfg["H"], cfg["S_q"], cfg["S_kv"], cfg["D"], cfg["causal"])
+
+    stream = torch.cuda.current_stream(dev)
+    step = lambda: binding.attn_fwd(qd, kd, vd, o, lse, causal=cfg["causal"], scale=scale, stream=stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # HIP events on the launch stream around every launch (kernel duration), wall clock around all K steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record(stream)
+        step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+    avg_kern_ms = float(np.mean(kern_ms))
+    ms_per_step = wall * 1e3 / args.steps
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (avg_kern_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "attention fwd TFLOP/s at 1 GPU (bf16, D=%d, S=%d, %s)" % (cfg["D"], cfg["S_q"], "causal" if cfg["causal"] else "non-causal"),
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg["name"], "B": cfg["B"], "H": cfg["H"], "S_q": cfg["S_q"], "S_kv": cfg["S_kv"],
+                   "D": cfg["D"], "causal": cfg["causal"], "flop_per_step": flops,
+                   "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+                   "kernel_ms_avg": avg_kern_ms, "kernel_ms_min": float(np.min(kern_ms)), "kernel_ms_median": float(np.median(kern_ms))},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, scale)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,80 @@
+/*
+ * attn_fwd.h -- C ABI of libmi355attn.so: Flash-Attention forward for MI355X (gfx950).
+ *
+ * The operation is the per-SM loop of the paper's Section 3 running example
+ * (Fig. 1a; its software-pipelined form is Fig. 1f):
+ *     O = 0;  for each K/V tile i:  S = gemm(Q, K[i]);  P = exp(S);  O += gemm(P, V[i])
+ * in its complete online-softmax form, i.e. with the running row maximum,
+ * the accumulator rescale and the final normalisation that Section 6.2 calls
+ * "softmax calculations" and "accumulator rescaling", plus the log-sum-exp of
+ * every row.  For b in [0,B), h in [0,H), i in [0,S_q):
+ *
+ *     J(i)   = { j : 0 <= j < S_kv }                  causal == 0
+ *            = { j : 0 <= j < S_kv, j <= i }          causal != 0 (top-left aligned)
+ *     s_ij   = scale * sum_d q[b,h,i,d] * k[b,h,j,d]
+ *     lse[b,h,i] = ln sum_{j in J(i)} exp(s_ij)
+ *     o[b,h,i,:] = sum_{j in J(i)} exp(s_ij - lse[b,h,i]) * v[b,h,j,:]
+ *
+ * Both contractions run on bf16 MFMA with fp32 accumulation; P is rounded to
+ * bf16 (round to nearest even) before the second contraction; the row sum is
+ * taken over the unrounded fp32 P.
+ *
+ * No C++ types, no exceptions and no torch types cross this boundary.
+ */
+#ifndef MI355_ATTN_FWD_H
+#define MI355_ATTN_FWD_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum attn_status {
+    ATTN_OK = 0,
+    ATTN_ERR_NULL = -1,          /* a required pointer is NULL */
+    ATTN_ERR_SHAPE = -2,         /* B, H, S_q or S_kv < 1, or a tensor exceeds 2^31-1 rows / 2^40 elements */
+    ATTN_ERR_UNSUPPORTED_D = -3, /* D not in {64, 128, 256} */
+    ATTN_ERR_ALIGN = -4,         /* q, k, v or o not 16-byte aligned, or lse not 4-byte aligned */
+    ATTN_ERR_SCALE = -5,         /* scale is NaN, infinite or negative */
+    ATTN_ERR_LAUNCH = -6         /* the HIP runtime refused the launch (see hipGetLastError) */
+} attn_status;
+
+/*
+ * attn_fwd -- enqueue one forward pass on `stream` and return (asynchronous).
+ *
+ *   q      device pointer, bf16, contiguous row-major [B][H][S_q][D]      (read only)
+ *   k, v   device pointers, bf16, contiguous row-major [B][H][S_kv][D]    (read only)
+ *   o      device pointer, bf16, [B][H][S_q][D]; every element is overwritten
+ *   lse    device pointer, fp32, [B][H][S_q]; natural-log log-sum-exp of the
+ *          scaled scores of each row; every element is overwritten
+ *   B, H, S_q, S_kv   >= 1, any value (ragged tiles are masked inside the kernel)
+ *   D      64, 128 or 256
+ *   causal 0: every key is visible; non-zero: key j is visible to query i iff j <= i
+ *   scale  multiplies QK^T before the softmax; finite and >= 0 (callers pass 1/sqrt(D))
+ *   stream a hipStream_t passed as void* (NULL = the default stream)
+ *
+ * Ownership: the caller owns all five buffers and keeps them alive until the
+ * work enqueued on `stream` has completed.  The library allocates nothing,
+ * keeps no state between calls and never synchronises the device.  o/lse must
+ * not overlap q/k/v.
+ *
+ * Errors: arguments are validated on the host before any HIP call; on a
+ * validation error a negative attn_status is returned and nothing is
+ * launched.  A launch the runtime rejects returns ATTN_ERR_LAUNCH.  The
+ * function never aborts or throws.  NaN/Inf inside q, k, v are not checked
+ * (the outputs are then unspecified).  Results are bitwise reproducible from
+ * run to run (no atomics).
+ */
+int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
+             int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+             void *stream);
+
+/* Static, NUL-terminated description of an attn_status value; never freed. */
+const char *attn_strerror(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355_ATTN_FWD_H */

@@ -5,11 +5,12 @@ running example (Fig. 1a / 1f), hand-written in HIP behind a C-ABI library.
 computes lives in `binding`, which raises at import time if the library has
 not been built (there is no CPU fallback).
 """
-__all__ = ["synth", "binding"]
+import importlib
+
+__all__ = ["synth", "binding", "attn_fwd", "attn_strerror", "attn_version"]
 
 
 def __getattr__(name):
-    if name in ("attn_fwd", "attn_strerror", "attn_version", "binding"):
-        from . import binding
-        return binding if name == "binding" else getattr(binding, name)
+    if name in ("attn_fwd", "attn_strerror", "attn_version"):
+        return getattr(importlib.import_module(__name__ + ".binding"), name)
     raise AttributeError(name)

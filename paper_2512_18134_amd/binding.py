@@ -1,0 +1,89 @@
+"""ctypes binding of libmi355attn.so: argument marshalling only.
+
+Same names as include/attn_fwd.h.  There is no fallback: importing this module
+raises if the library has not been built (python -m paper_2512_18134_amd.build).
+PyTorch appears only as the owner of device memory and of the stream.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmi355attn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libmi355attn.so is not built: run `python -m paper_2512_18134_amd.build` "
+        "(there is no CPU or PyTorch fallback for attn_fwd)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_lib.attn_fwd.restype = ctypes.c_int
+_lib.attn_fwd.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
+_lib.attn_strerror.restype = ctypes.c_char_p
+_lib.attn_strerror.argtypes = [ctypes.c_int]
+_lib.attn_version.restype = ctypes.c_int
+_lib.attn_version.argtypes = []
+
+ATTN_OK = 0
+ATTN_ERR_NULL = -1
+ATTN_ERR_SHAPE = -2
+ATTN_ERR_UNSUPPORTED_D = -3
+ATTN_ERR_ALIGN = -4
+ATTN_ERR_SCALE = -5
+ATTN_ERR_LAUNCH = -6
+
+
+class AttnError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__("attn_fwd: %s (status %d)" % (attn_strerror(status), status))
+
+
+def attn_strerror(status):
+    return _lib.attn_strerror(int(status)).decode()
+
+
+def attn_version():
+    return int(_lib.attn_version())
+
+
+def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S_q, S_kv, D, causal, scale, stream_ptr):
+    """The C entry point with raw integer addresses; returns the attn_status."""
+    return int(_lib.attn_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S_q, S_kv, D,
+                             int(bool(causal)), float(scale), stream_ptr))
+
+
+def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
+    """attn_fwd on torch device tensors.
+
+    q [B,H,S_q,D], k/v [B,H,S_kv,D]: contiguous bf16 on the GPU.  o (bf16) and
+    lse (fp32 [B,H,S_q]) are allocated when not given.  The launch goes to
+    `stream` (default: torch's current stream) and is asynchronous.
+    Returns (o, lse).
+    """
+    import torch
+
+    for t in (q, k, v):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise TypeError("q, k, v must be contiguous 4-D bf16 tensors on the GPU")
+    B, H, S_q, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
+        raise ValueError("q, k, v shapes do not agree")
+    S_kv = k.shape[2]
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, S_q), dtype=torch.float32, device=q.device)
+    if o.dtype != torch.bfloat16 or o.shape != q.shape or not o.is_contiguous() or not o.is_cuda:
+        raise TypeError("o must be a contiguous bf16 GPU tensor shaped like q")
+    if lse.dtype != torch.float32 or tuple(lse.shape) != (B, H, S_q) or not lse.is_contiguous() or not lse.is_cuda:
+        raise TypeError("lse must be a contiguous fp32 GPU tensor [B,H,S_q]")
+    if scale is None:
+        scale = 1.0 / float(D) ** 0.5
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    with torch.cuda.device(q.device):
+        rc = attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                          B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
+    if rc != ATTN_OK:
+        raise AttnError(rc)
+    return o, lse

@@ -1,0 +1,74 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol that
+include/attn_fwd.h declares, and validates arguments on the host before any
+HIP call (so a validation error launches nothing)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "attn_fwd.h")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2512_18134_amd import binding as b
+    return b
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(binding):
+    names = declared_symbols()
+    assert {"attn_fwd", "attn_strerror", "attn_version"} <= set(names)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), "symbol %s missing from libmi355attn.so" % n
+
+
+def test_version_and_strerror(binding):
+    assert binding.attn_version() >= 100
+    for code in range(0, -7, -1):
+        msg = binding.attn_strerror(code)
+        assert isinstance(msg, str) and msg and "unknown" not in msg
+    assert "unknown" in binding.attn_strerror(-99)
+
+
+def test_validation_happens_before_any_launch(binding):
+    b = binding
+    ok = 0x1000  # aligned, non-NULL fake addresses: never dereferenced on a validation error
+    f = lambda **kw: b.attn_fwd_raw(*[kw.get(n, d) for n, d in (
+        ("q", ok), ("k", ok), ("v", ok), ("o", ok), ("lse", ok), ("B", 1), ("H", 1), ("S_q", 8), ("S_kv", 8),
+        ("D", 64), ("causal", 0), ("scale", 0.125), ("stream", 0))])
+    for name in ("q", "k", "v", "o", "lse"):
+        assert f(**{name: 0}) == b.ATTN_ERR_NULL
+    for name in ("B", "H", "S_q", "S_kv"):
+        assert f(**{name: 0}) == b.ATTN_ERR_SHAPE
+        assert f(**{name: -3}) == b.ATTN_ERR_SHAPE
+    assert f(B=1 << 20, H=1 << 20) == b.ATTN_ERR_SHAPE
+    for D in (0, 32, 96, 127, 512):
+        assert f(D=D) == b.ATTN_ERR_UNSUPPORTED_D
+    for name in ("q", "k", "v", "o"):
+        assert f(**{name: ok + 8}) == b.ATTN_ERR_ALIGN
+    assert f(lse=ok + 2) == b.ATTN_ERR_ALIGN
+    for s in (float("nan"), float("inf"), -1.0):
+        assert f(scale=s) == b.ATTN_ERR_SCALE
+
+
+def test_product_package_does_not_import_the_oracle():
+    # the HIP path and the oracle share nothing and neither imports the other
+    pkg = os.path.join(ROOT, "paper_2512_18134_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".hpp", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|attn_ref|libattn_ref", text, flags=re.M), fn
+    for fn in os.listdir(os.path.join(ROOT, "oracle")):
+        if fn.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", fn)).read()
+            assert "paper_2512_18134_amd" not in text and "attn_fwd.h" not in text, fn
