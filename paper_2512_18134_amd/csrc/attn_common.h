@@ -1,0 +1,66 @@
+// attn_common.h -- vector types, the LDS swizzle and the kernel parameter block
+// shared by the attention-forward kernels of this library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+namespace attn {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+#define ATTN_LDS_PTR(T) __attribute__((address_space(3))) T *
+
+constexpr int kNumXcd = 8;  // MI355X: 8 XCDs; workgroup ids are dealt to them round-robin
+
+// 16-byte-chunk XOR swizzle of a K/V tile row in LDS (`row` = key index inside
+// the tile; the value is XORed into the low 4 bits of the chunk index).
+//   * ds_read_b128 of one chunk column over 16 consecutive rows (K as MFMA A
+//     operand) touches 16 different 16-byte bank groups;
+//   * the transposing 8-byte reads of V touch rows r..r+3 in four different
+//     64-byte bank groups.
+template <int D>
+__device__ __forceinline__ int swz(int row)
+{
+    const int x = (D == 64) ? (row >> 1) : row;
+    if (D == 64)
+        return ((x & 1) << 2) | ((x >> 1) & 3);
+    return ((x & 3) << 2) | ((x >> 2) & 3);
+}
+
+// max / sum partner: the lane that holds the other 16 keys of the same query
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+// MFMA 32x32x16 bf16 accumulator layout: register r of lane l is
+// row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+__device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+
+// workgroup id -> logical id such that every XCD owns a contiguous range of
+// logical ids (all query tiles of a head then share one XCD's L2 while they
+// stream the same K/V).
+__device__ __forceinline__ int xcd_remap(int wid, int total)
+{
+    const int per = total / kNumXcd, rem = total % kNumXcd;
+    const int xcd = wid % kNumXcd, slot = wid / kNumXcd;
+    return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + slot;
+}
+
+// Kernel parameters (plain struct, passed by value).
+struct Params {
+    const bf16_t *q, *k, *v;
+    bf16_t *o;
+    float *lse;
+    int S_q, S_kv;
+    int n_qt;      // query tiles per (b,h)
+    int total_wg;  // B*H*n_qt
+    float c;       // scale * log2(e): the softmax runs in the base-2 domain
+    float scale;
+};
+
+}  // namespace attn
