@@ -49,11 +49,8 @@ __device__ __forceinline__ void wait_vmcnt()
 
 __device__ __forceinline__ float lane_pair_max(float x)
 {
-    // v_permlane32_swap: afterwards one result holds the low half's value in
-    // all 64 lanes and the other the high half's; their max is the pair max.
-    const uint32_t u = __builtin_bit_cast(uint32_t, x);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+    // max over the two lanes (l, l^32) that share a query column
+    return fmaxf(x, xor32(x));
 }
 
 // Template parameters:

@@ -190,11 +190,27 @@ def test_joint_permutation_invariance_and_determinism(B):
     assert np.max(np.abs(l1 - l2)) <= 1e-4
 
 
-def test_sharp_softmax_small(B):
-    # the rescale path: scores of several hundred, near one-hot rows
-    q, k, v = synth.make_qkv(1, 2, 513, 513, 256, seed=12, sharp=True)
+@pytest.mark.parametrize("D", [64, 128, 256])
+def test_sharp_softmax_small(B, D):
+    # the rescale path: scores of several hundred, near one-hot rows; a row maximum
+    # that is wrong by even one key overflows exp2 here
+    q, k, v = synth.make_qkv(1, 2, 513, 513, D, seed=12, sharp=True)
     for causal in (False, True):
-        check_full(B, q, k, v, causal, synth.default_scale(256), "sharp causal=%s" % causal)
+        check_full(B, q, k, v, causal, synth.default_scale(D), "sharp D=%d causal=%s" % (D, causal))
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_row_max_in_either_lane_half(B, D):
+    # one key per 64-key tile carries a huge score; its position walks through all 64
+    # slots of a tile, i.e. through both lane halves and every accumulator register
+    s = 64 * 64
+    q = np.zeros((1, 1, 64, D), np.float32)
+    q[..., 0] = 16.0
+    k = np.zeros((1, 1, s, D), np.float32)
+    for t in range(64):
+        k[0, 0, 64 * t + t, 0] = 4.0 + 0.25 * t      # scaled score 64..127, growing tile by tile
+    _, _, v = synth.make_qkv(1, 1, 64, s, D, seed=15)
+    check_full(B, bf16(q), bf16(k), v, False, 1.0, "max walks D=%d" % D)
 
 
 def test_increasing_scores_force_rescale_every_tile(B):
