@@ -19,8 +19,22 @@ HIPCC_FLAGS = [
 ]
 
 
+def generate_sources(verbose=False):
+    """Run the loop generator: csrc/generated/attn_loop_d{64,128}.inc."""
+    gen = os.path.join(HERE, "csrc", "gen_attn_loop.py")
+    out_dir = os.path.join(HERE, "csrc", "generated")
+    os.makedirs(out_dir, exist_ok=True)
+    for d in (64, 128):
+        out = os.path.join(out_dir, "attn_loop_d%d.inc" % d)
+        cmd = [sys.executable, gen, str(d), out]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+
+
 def build_library(verbose=False):
-    """Compile every HIP source into LIB_PATH.  Raises on failure."""
+    """Generate the scheduled loops, then compile every HIP source into LIB_PATH.  Raises on failure."""
+    generate_sources(verbose)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB_PATH + ".tmp.%d" % os.getpid()
     cmd = [hipcc] + HIPCC_FLAGS + ["-o", tmp] + SOURCES

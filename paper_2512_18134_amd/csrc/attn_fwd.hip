@@ -7,6 +7,7 @@
 #include <type_traits>
 
 #include "attn_fwd.h"
+#include "attn_fwd_asm.h"
 #include "attn_fwd_pipe.h"
 #include "attn_fwd_simple.h"
 
@@ -60,16 +61,30 @@ int launch_pipe(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_pipe_kernel<D, BN, NW, QB, PIPE, false>, p, BH, NW * 32 * QB, NW * 64, LDS, stream);
 }
 
+template <int D>
+int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
+{
+    constexpr int LDS = 8 * 64 * D * 2;
+    if (causal)
+        return launch(attn::attn_fwd_asm_kernel<D, true>, p, BH, 256, 512, LDS, stream);
+    return launch(attn::attn_fwd_asm_kernel<D, false>, p, BH, 256, 512, LDS, stream);
+}
+
 // Debug only: ATTN_FWD_VARIANT picks a tiling / schedule variant of the pipelined kernel.
 template <int D>
 int launch_pipe_variant(int variant, const Params &p, int BH, int causal, hipStream_t stream)
 {
     switch (variant) {
+    case 1:
+        return launch_pipe<D, 64, 8, 1, 1>(p, BH, causal, stream);
     case 2:
         return launch_pipe<D, 64, 8, 1, 2>(p, BH, causal, stream);
     case 3:
         return launch_pipe<D, 64, 8, 1, 3>(p, BH, causal, stream);
     default:
+        // the hand-scheduled loop masks scores before the multiply by scale*log2e: it needs scale > 0
+        if (p.scale > 0.f)
+            return launch_asm<D>(p, BH, causal, stream);
         return launch_pipe<D, 64, 8, 1, 1>(p, BH, causal, stream);
     }
 }
