@@ -8,7 +8,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmi355attn.so")
+# ATTN_FWD_LIB (debug only) loads another build of the same library, e.g. a schedule experiment
+LIB_PATH = os.environ.get("ATTN_FWD_LIB", os.path.join(_HERE, "libmi355attn.so"))
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

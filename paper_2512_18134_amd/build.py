@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "attn_fwd.hip")]
-LIB_PATH = os.path.join(HERE, "libmi355attn.so")
+LIB_PATH = os.environ.get("ATTN_FWD_LIB_OUT", os.path.join(HERE, "libmi355attn.so"))  # override: experiments only
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

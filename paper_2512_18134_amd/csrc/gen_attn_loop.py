@@ -37,6 +37,7 @@ Hazards handled by construction (the assembler inserts no wait states):
 
 usage: gen_attn_loop.py <D> <out.inc>
 """
+import os
 import sys
 
 
@@ -100,7 +101,8 @@ class Gen:
         self.s_t0 = 52            # s[52:53] scratch pair
         self.s_t2 = 54
         self.lines = []
-        self.uid = 0
+        # timing experiments only (results are wrong with any of these set): drop parts of the loop
+        self.exp = set(filter(None, os.environ.get("ATTN_GEN_EXP", "").split(",")))
 
     # ------------------------------------------------------------------ helpers
     def e(self, s):
@@ -127,6 +129,8 @@ class Gen:
         """LDS reads that bring the A operand of `op` into fragment buffer `buf`."""
         f = self.FR + 4 * buf
         kind, a, b = op
+        if "nolds" in self.exp:
+            return []
         if kind == "pv":
             kc, db = a, b
             off = vst * self.TB + kc * 16 * self.ROWB
@@ -153,6 +157,8 @@ class Gen:
     def max_ops(self, S_cur):
         """Row max of the lane's 32 scores into T, two interleaved max3 chains."""
         ops = []
+        if "nomax" in self.exp:
+            return []
         ch = [[], []]
         for c, mx in enumerate((self.MX0, self.MX1)):
             s = [S_cur + 16 * c + i for i in range(16)]
@@ -169,6 +175,8 @@ class Gen:
         """Lane-pair max, new running max, and the branch to the rare rescale path."""
         T, TMP2, DD = self.T, self.TMP2, self.DD
         t0 = self.sr(self.s_t0, 2)
+        if "nomax" in self.exp:
+            return ["%s:" % self.lab("RESCRET%d_" % b)]
         return [
             "v_mov_b32 v%d, v%d" % (TMP2, T),
             "s_nop 1",
@@ -195,6 +203,8 @@ class Gen:
             return ["v_add_f32 v%d, v%d, v%d" % (self.LA, self.LA, S_cur + 2 * k),
                     "v_add_f32 v%d, v%d, v%d" % (self.LB, self.LB, S_cur + 2 * k + 1),
                     "v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (P_new + k, S_cur + 2 * k, S_cur + 2 * k + 1)]
+        if "novalu" in self.exp:
+            return []
         for t in range(16 + 2):
             if t < 16:
                 ops += F(t)
@@ -211,6 +221,9 @@ class Gen:
         ptr = self.s_kptr if which == "k" else self.s_vptr
         out = []
         for i in range(self.NLD):
+            if "nodma" in self.exp:
+                out.append([])
+                continue
             out.append(["s_add_u32 m0, s%d, %d" % (lds, stage * self.TB + i * 8192),
                         "s_nop 0",
                         "global_load_lds_dwordx4 v%d, %s" % (self.DVOFF + i, self.sr(ptr, 2))])
@@ -253,10 +266,11 @@ class Gen:
             issue(i, mfmas[i], kst, vst)
         for i, op in enumerate(mfmas):
             # wait until every read of operand i has returned (reads return in order)
-            last = max(p for p, x in enumerate(self.outstanding) if x == i)
-            after = len(self.outstanding) - 1 - last
-            self.e("s_waitcnt lgkmcnt(%d)" % after)
-            self.outstanding = self.outstanding[last + 1:]
+            if "nolds" not in self.exp:
+                last = max(p for p, x in enumerate(self.outstanding) if x == i)
+                after = len(self.outstanding) - 1 - last
+                self.e("s_waitcnt lgkmcnt(%d)" % after)
+                self.outstanding = self.outstanding[last + 1:]
             self.e(self.mfma_text(op, i % NF, P_prev, S_nxt))
             j = i + PFD
             if j < n:
@@ -270,7 +284,7 @@ class Gen:
                 self.e(ins)
         # rename the next iteration's prefetches to its own numbering
         self.outstanding = [x - 1000 for x in self.outstanding]
-        assert all(0 <= x < PFD for x in self.outstanding), self.outstanding
+        assert "nolds" in self.exp or all(0 <= x < PFD for x in self.outstanding), self.outstanding
 
     # --------------------------------------------------------------- the loop
     def body(self, b):
@@ -288,8 +302,9 @@ class Gen:
         self.e("s_cbranch_scc1 %s" % L("MASK%d_" % b))
         self.e("%s:" % L("MASKRET%d_" % b))
         # loads of the previous iteration may stay in flight; everything older has landed
-        self.e("s_waitcnt vmcnt(%d)" % (2 * NLD))
-        self.e("s_barrier")
+        if "nobar" not in self.exp:
+            self.e("s_waitcnt vmcnt(%d)" % (2 * NLD))
+            self.e("s_barrier")
         # ---- VALU program, dealt out over the slots
         a_ops = self.max_ops(S_cur) + self.decide_ops(b)
         b_ops = self.pair_ops(S_cur, P_new)
