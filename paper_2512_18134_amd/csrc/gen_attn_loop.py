@@ -259,6 +259,8 @@ class Gen:
         NF, PFD = self.NF, self.PFD
         n = len(mfmas)
         def issue(idx, op, k, v):
+            if "halflds" in self.exp and idx % 2 == 1:
+                return
             for ins in self.frag_loads(op, idx % NF, k, v):
                 self.e(ins)
                 self.outstanding.append(idx)
@@ -266,7 +268,7 @@ class Gen:
             issue(i, mfmas[i], kst, vst)
         for i, op in enumerate(mfmas):
             # wait until every read of operand i has returned (reads return in order)
-            if "nolds" not in self.exp:
+            if "nolds" not in self.exp and any(x == i for x in self.outstanding):
                 last = max(p for p, x in enumerate(self.outstanding) if x == i)
                 after = len(self.outstanding) - 1 - last
                 self.e("s_waitcnt lgkmcnt(%d)" % after)
@@ -394,7 +396,7 @@ class Gen:
         pv = [("pv", kc, db) for kc in range(4) for db in range(self.DB)]
         self.e("%s:" % L("EXIT%d_" % b))
         # the prefetched operands belong to the interleaved order (first half of PV only): same ops
-        self.outstanding = [i for i in range(self.PFD) for _ in range(2)]
+        self.outstanding = [i for i in range(self.PFD) for _ in range(2) if not ("halflds" in self.exp and i % 2 == 1)]
         self.stream(pv, P_prev, 0, 0, vst, {}, {}, self.PFD, None)
         self.e("s_branch %s" % L("DONE_"))
 
@@ -497,6 +499,6 @@ class Gen:
 
 if __name__ == "__main__":
     D = int(sys.argv[1])
-    text = Gen(D).emit_inc()
+    text = Gen(D, PFD=int(os.environ.get("ATTN_GEN_PFD", "3"))).emit_inc()
     with open(sys.argv[2], "w") as f:
         f.write(text)
