@@ -30,6 +30,13 @@ def generate_sources(verbose=False):
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
+    gen2 = os.path.join(HERE, "csrc", "gen_attn_loop2.py")
+    for name in ("d128a", "d256a"):
+        out = os.path.join(out_dir, "attn_loop_%s.inc" % name)
+        cmd = [sys.executable, gen2, name, out]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
 
 
 def build_library(verbose=False):

@@ -8,6 +8,7 @@
 
 #include "attn_fwd.h"
 #include "attn_fwd_asm.h"
+#include "attn_fwd_asm2.h"
 #include "attn_fwd_pipe.h"
 #include "attn_fwd_simple.h"
 
@@ -70,11 +71,24 @@ int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_asm_kernel<D, false>, p, BH, 256, 512, LDS, stream);
 }
 
+template <int D, int QB>
+int launch_asm2(const Params &p, int BH, int causal, hipStream_t stream)
+{
+    constexpr int LDS = 8 * 32 * D * 2;
+    if (causal)
+        return launch(attn::attn_fwd_asm2_kernel<D, QB, true>, p, BH, 128 * QB, 256, LDS, stream);
+    return launch(attn::attn_fwd_asm2_kernel<D, QB, false>, p, BH, 128 * QB, 256, LDS, stream);
+}
+
 // Debug only: ATTN_FWD_VARIANT picks a tiling / schedule variant of the pipelined kernel.
 template <int D>
 int launch_pipe_variant(int variant, const Params &p, int BH, int causal, hipStream_t stream)
 {
     switch (variant) {
+    case 4:
+        if (D == 128 && p.scale > 0.f)
+            return launch_asm2<128, 2>(p, BH, causal, stream);
+        return launch_pipe<D, 64, 8, 1, 1>(p, BH, causal, stream);
     case 1:
         return launch_pipe<D, 64, 8, 1, 1>(p, BH, causal, stream);
     case 2:
@@ -143,6 +157,8 @@ extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, fl
         return pipe_ok ? launch_pipe_variant<128>(variant, p, (int)BH, causal, st)
                        : launch_simple<128, 64, 8>(p, (int)BH, causal, st);
     default:
+        if (!force_simple && variant == 0 && scale > 0.f && ((long long)S_kv * D * 2 < (1LL << 31)))
+            return launch_asm2<256, 1>(p, (int)BH, causal, st);
         return launch_simple<256, 32, 4>(p, (int)BH, causal, st);
     }
 }
