@@ -1,0 +1,238 @@
+"""Small optimal modulo scheduler, in the vocabulary of the paper's Section 3.1.
+
+Host-side model only (no GPU work): it checks the claim that the loop order the
+hand-scheduled kernels use is what modulo scheduling yields for the measured
+gfx950 costs, and reproduces the paper's running example.
+
+  * A loop is a dependence graph G = (V, E).  Every instruction v has a resource
+    reservation table RRT[v]: a list with one entry per cycle of its execution,
+    each entry a dict {functional unit: instances occupied}.  The machine
+    description D gives the capacity of every unit.
+  * An edge (u, v, d, delta): v of iteration i issues at least d cycles after u of
+    iteration i - delta.
+  * A modulo schedule is (M, I): instruction v issues at cycles M[v], I + M[v], ...;
+    it is valid iff M[v] + I*delta >= M[u] + d for every edge and the modular RRT
+    (unit use at every cycle mod I) stays within D.
+  * L = length of M (last busy cycle + 1).  The pipelined loop overlaps
+    ceil(L/I) copies of M, I cycles apart: the first (ceil(L/I) - 1) * I cycles
+    are the prologue, the next I the steady state, the rest the epilogue.
+
+The search is exhaustive (smallest I first, then smallest L): graphs here have a
+handful of tile-level instructions, which is the granularity the paper
+schedules at.  Costs are normalised first (Section 5.2): integers C' with
+sum <= U whose pairwise ratios stay as close as possible to those of C.
+"""
+import itertools
+import math
+
+
+class Loop:
+    def __init__(self, capacity):
+        self.capacity = dict(capacity)   # machine description D
+        self.rrt = {}                    # name -> list of {unit: count}
+        self.edges = []                  # (u, v, d, delta)
+        self.order = []
+
+    def op(self, name, unit, cycles, count=1):
+        """Instruction that occupies `count` instances of `unit` for `cycles` cycles."""
+        assert unit in self.capacity and cycles >= 0
+        self.rrt[name] = [{unit: count} for _ in range(cycles)]
+        self.order.append(name)
+        return name
+
+    def dep(self, u, v, d=None, delta=0):
+        """v needs u's result: by default d = execution time of u."""
+        self.edges.append((u, v, len(self.rrt[u]) if d is None else d, delta))
+
+
+def modular_rrt(loop, M, I):
+    """Unit use in the steady state: table[cycle mod I][unit]."""
+    table = [dict() for _ in range(I)]
+    for v, start in M.items():
+        for c, use in enumerate(loop.rrt[v]):
+            row = table[(start + c) % I]
+            for unit, n in use.items():
+                row[unit] = row.get(unit, 0) + n
+    return table
+
+
+def is_valid(loop, M, I):
+    for u, v, d, delta in loop.edges:
+        if M[v] + I * delta < M[u] + d:
+            return False
+    for row in modular_rrt(loop, M, I):
+        for unit, n in row.items():
+            if n > loop.capacity[unit]:
+                return False
+    return True
+
+
+def length(loop, M):
+    return max(M[v] + max(1, len(loop.rrt[v])) for v in M)
+
+
+def res_mii(loop):
+    """Resource bound on I: total occupation of a unit / its capacity."""
+    use = {}
+    for v in loop.rrt:
+        for row in loop.rrt[v]:
+            for unit, n in row.items():
+                use[unit] = use.get(unit, 0) + n
+    return max([1] + [math.ceil(n / loop.capacity[u]) for u, n in use.items()])
+
+
+def rec_mii(loop):
+    """Recurrence bound on I: max over dependence cycles of ceil(sum d / sum delta) (small graphs: brute force)."""
+    names = list(loop.rrt)
+    best = 1
+    adj = {}
+    for u, v, d, delta in loop.edges:
+        adj.setdefault(u, []).append((v, d, delta))
+    def walk(start, node, dsum, delsum, seen):
+        nonlocal best
+        for v, d, delta in adj.get(node, []):
+            if v == start:
+                if delsum + delta > 0:
+                    best = max(best, math.ceil((dsum + d) / (delsum + delta)))
+            elif v not in seen:
+                walk(start, v, dsum + d, delsum + delta, seen | {v})
+    for s in names:
+        walk(s, s, 0, 0, {s})
+    return best
+
+
+def optimal_modulo_schedule(loop, I, max_len):
+    """Valid M with initiation interval I and the smallest length <= max_len, or None."""
+    names = loop.order
+    for L in range(1, max_len + 1):
+        ranges = [range(0, L - max(1, len(loop.rrt[v])) + 1) for v in names]
+        for starts in itertools.product(*ranges):
+            M = dict(zip(names, starts))
+            if length(loop, M) == L and is_valid(loop, M, I):
+                return M
+    return None
+
+
+def schedule(loop, max_len=None):
+    """Smallest I, then smallest L: returns (M, I, L)."""
+    total = sum(max(1, len(r)) for r in loop.rrt.values())
+    max_len = max_len or 2 * total
+    I = max(res_mii(loop), rec_mii(loop))
+    while True:
+        M = optimal_modulo_schedule(loop, I, max_len)
+        if M is not None:
+            return M, I, length(loop, M)
+        I += 1
+
+
+def in_order_interval(loop):
+    """Cycles per iteration when the loop body runs in program order without overlap."""
+    t = 0
+    finish = {}
+    for v in loop.order:
+        start = t
+        for u, w, d, delta in loop.edges:
+            if w == v and delta == 0 and u in finish:
+                start = max(start, finish[u][0] + d)
+        finish[v] = (start, start + max(1, len(loop.rrt[v])))
+        t = start + max(1, len(loop.rrt[v]))
+    return t
+
+
+def pipeline_code(loop, M, I):
+    """Prologue / steady state / epilogue as lists of (instruction, iteration offset), by issue cycle.
+
+    Iteration offset k in the steady state means "the instance that belongs k iterations
+    before the newest one in flight" (Fig. 1f: Sn is offset 0, P and O are offset 1).
+    """
+    L = length(loop, M)
+    copies = math.ceil(L / I)
+    stage = {v: M[v] // I for v in M}
+    steady = sorted(((M[v] % I, v, stage[v]) for v in M))
+    prologue = []
+    for c in range(copies - 1):                     # copy c starts at cycle c*I
+        for v in M:
+            pass
+    for cyc in range((copies - 1) * I):
+        for v in loop.order:
+            for c in range(copies):
+                if c * I + M[v] == cyc:
+                    prologue.append((cyc, v, c))
+    return {"copies": copies, "prologue_cycles": (copies - 1) * I,
+            "prologue": prologue, "steady": [(c, v, k) for c, v, k in steady]}
+
+
+def normalise_costs(C, U):
+    """Section 5.2: integers C' (sum in [1, U]) minimising F with |C[i]C'[j] - C[j]C'[i]| <= F for all i, j.
+
+    Exhaustive over the scale of the largest entry (every optimum has C' close to a scaled C)."""
+    n = len(C)
+    big = max(range(n), key=lambda i: C[i])
+    best = None
+    for top in range(1, U + 1):
+        # candidates: round each entry to one of the two integers around its scaled value
+        scaled = [C[i] * top / C[big] for i in range(n)]
+        choices = [sorted({max(0, math.floor(s)), math.ceil(s)}) for s in scaled]
+        for cand in itertools.product(*choices):
+            if not (1 <= sum(cand) <= U):
+                continue
+            F = max(abs(C[i] * cand[j] - C[j] * cand[i]) for i in range(n) for j in range(n))
+            # prefer smaller F relative to the scale (F grows with the scale), then finer resolution
+            key = (F / max(1, sum(cand)), -sum(cand))
+            if best is None or key < best[0]:
+                best = (key, list(cand), F)
+    return best[1], best[2]
+
+
+# ------------------------------------------------------------------ the paper's running example
+def paper_toy():
+    """Fig. 1: S = gemm(Q,K) on the tensor core, P = exp(S) on the exp unit, O += gemm(P,V) on the
+    tensor core; every instruction one cycle; O carries a dependence to the next iteration."""
+    g = Loop({"TC": 1, "EXP": 1})
+    g.op("S", "TC", 1)
+    g.op("P", "EXP", 1)
+    g.op("O", "TC", 1)
+    g.dep("S", "P")
+    g.dep("P", "O")
+    g.dep("O", "O", delta=1)
+    return g
+
+
+# ------------------------------------------------------------------ the gfx950 loop
+# Measured per-wave costs at D = 128, 64-key tile, 32 query rows per wave, in matrix-pipe cycles:
+# 16 MFMAs of 32 cycles for each product; the softmax of the tile's 32 scores per lane is ~137 VALU
+# instructions, ~790 cycles when one wave issues them alone; LDS operand reads ~200 cycles of the LDS port.
+GFX950_D128 = {"QK": 512, "SM": 790, "PV": 512, "LDS_K": 90, "LDS_V": 115}
+
+
+def gfx950_attention(costs=GFX950_D128, U=24):
+    """Tile-level dependence graph of one wave of the attention loop on gfx950: the matrix pipe (MFMA),
+    the VALU and the LDS port are separate units fed from one instruction stream; global->LDS loads are
+    streaming operations (zero latency in the model, Section 5.3) and do not appear."""
+    names = ["LDS_K", "QK", "SM", "LDS_V", "PV"]
+    Cn, F = normalise_costs([costs[n] for n in names], U)
+    c = dict(zip(names, Cn))
+    g = Loop({"MFMA": 1, "VALU": 1, "LDS": 1})
+    g.op("LDS_K", "LDS", c["LDS_K"])
+    g.op("QK", "MFMA", c["QK"])
+    g.op("SM", "VALU", c["SM"])
+    g.op("LDS_V", "LDS", c["LDS_V"])
+    g.op("PV", "MFMA", c["PV"])
+    g.dep("LDS_K", "QK", d=1)       # fragments stream into the MFMAs: the first one must have arrived
+    g.dep("QK", "SM")
+    g.dep("SM", "PV")
+    g.dep("LDS_V", "PV", d=1)
+    g.dep("SM", "SM", delta=1)      # running max / row sum
+    g.dep("PV", "PV", delta=1)      # accumulator O
+    return g, c, F
+
+
+if __name__ == "__main__":
+    g = paper_toy()
+    M, I, L = schedule(g)
+    print("paper toy: I=%d L=%d M=%s  in-order interval=%d" % (I, L, M, in_order_interval(g)))
+    g, c, F = gfx950_attention()
+    M, I, L = schedule(g, max_len=4 * sum(c.values()))
+    print("gfx950 D=128 wave: normalised costs %s (F=%d)" % (c, F))
+    print("  I=%d (MFMA-bound: %d)  L=%d  stages=%d  M=%s" % (I, c["QK"] + c["PV"], L, math.ceil(L / I), M))
+    print("  in-order interval=%d  => pipelining gain %.2fx" % (in_order_interval(g), in_order_interval(g) / I))
