@@ -2,9 +2,15 @@
 """Bench: Flash-Attention forward on one MI355X, headline workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+    python bench.py --paper-seq 16384 [--dtype f16]     # the paper's own sweep shape (Section 6.2)
 
 A "step" is one attn_fwd call (the whole hot path) over one batch of seeded
 synthetic Q/K/V that is already resident in HBM.  Prints ONE JSON line.
+
+--paper-seq S times the shape of the paper's forward-attention figures instead
+(BATCH=4, NUM_HEADS=32, HEAD_DIM=128, non-causal, S queries and keys, fp16 by
+default): N(0,1) values drawn on the device with torch's seeded generator (the
+host generator would need minutes for 3 x 268M elements at S = 16384).
 """
 import argparse
 import json
@@ -43,7 +49,7 @@ def cpu_baseline(cfg, q, k, v, scale, target_seconds=15.0):
     def run(n):
         rows = np.sort(rng.choice(total_rows, size=min(n, total_rows), replace=False)).astype(np.int64)
         t0 = time.perf_counter()
-        attn_oracle.attn_ref(q, k, v, cfg["causal"], scale, rows=rows)
+        attn_oracle.attn_ref(q, k, v, cfg["causal"], scale, rows=rows, dtype=cfg.get("dtype", "bf16"))
         dt = time.perf_counter() - t0
         i = rows % cfg["S_q"]
         pairs = np.minimum(i + 1, cfg["S_kv"]).sum() if cfg["causal"] else len(rows) * cfg["S_kv"]
@@ -62,6 +68,10 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="index into the baseline configs (3 = headline D=128 S=16384)")
+    ap.add_argument("--paper-seq", type=int, default=0,
+                    help="time the paper's Section 6.2 shape (B=4, H=32, D=128, non-causal) at this sequence length")
+    ap.add_argument("--dtype", choices=["bf16", "f16"], default=None,
+                    help="element type (default: bf16 for --config, f16 for --paper-seq)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB device copy instead (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -86,16 +96,36 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": args.steps}))
         return
-    cfg, q, k, v, scale = synth.make_config(args.config)
     dev = torch.device("cuda:0")
-    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
-    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    if args.paper_seq:
+        cfg = synth.paper_workload(args.paper_seq, causal=False)
+        cfg["dtype"] = args.dtype or "f16"
+        cfg["name"] = cfg["name"].replace("_f16", "_" + cfg["dtype"])
+        tdt = torch.float16 if cfg["dtype"] == "f16" else torch.bfloat16
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg["seed"])
+        draw = lambda S: torch.cat([torch.randn((1, cfg["H"], S, cfg["D"]), generator=gen, device=dev,
+                                                dtype=torch.float32).to(tdt) for _ in range(cfg["B"])])
+        qd, kd, vd = draw(cfg["S_q"]), draw(cfg["S_kv"]), draw(cfg["S_kv"])
+        scale = synth.default_scale(cfg["D"])
+        q = k = v = None
+    else:
+        cfg, q, k, v, scale = synth.make_config(args.config)
+        cfg = dict(cfg, dtype=args.dtype or "bf16")
+        tdt = torch.float16 if cfg["dtype"] == "f16" else torch.bfloat16
+        if cfg["dtype"] == "f16":
+            q, k, v = synth.make_qkv(cfg["B"], cfg["H"], cfg["S_q"], cfg["S_kv"], cfg["D"], cfg["seed"], cfg["sharp"],
+                                     dtype="f16")
+            cfg["name"] += "_f16"
+        to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(tdt)
+        qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    entry = binding.attn_fwd_f16 if cfg["dtype"] == "f16" else binding.attn_fwd
     o = torch.empty_like(qd)
     lse = torch.empty(qd.shape[:3], dtype=torch.float32, device=dev)
     flops = synth.attention_flops(cfg["B"], cfg["H"], cfg["S_q"], cfg["S_kv"], cfg["D"], cfg["causal"])
 
     stream = torch.cuda.current_stream(dev)
-    step = lambda: binding.attn_fwd(qd, kd, vd, o, lse, causal=cfg["causal"], scale=scale, stream=stream)
+    step = lambda: entry(qd, kd, vd, o, lse, causal=cfg["causal"], scale=scale, stream=stream)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -115,10 +145,10 @@ def main():
     achieved = flops / (avg_kern_ms * 1e-3) / 1e12
 
     out = {
-        "metric": "attention fwd TFLOP/s at 1 GPU (bf16, D=%d, S=%d, %s)" % (cfg["D"], cfg["S_q"], "causal" if cfg["causal"] else "non-causal"),
+        "metric": "attention fwd TFLOP/s at 1 GPU (%s, D=%d, S=%d, %s)" % (cfg["dtype"], cfg["D"], cfg["S_q"], "causal" if cfg["causal"] else "non-causal"),
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": cfg["name"], "B": cfg["B"], "H": cfg["H"], "S_q": cfg["S_q"], "S_kv": cfg["S_kv"],
                    "D": cfg["D"], "causal": cfg["causal"], "flop_per_step": flops,
                    "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
@@ -127,6 +157,8 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg["name"])},
     }
     if not args.no_cpu_baseline:
+        if q is None:  # device-generated inputs: the oracle reads the same bits back
+            q, k, v = (t.cpu().view(torch.int16).numpy().view(np.uint16) for t in (qd, kd, vd))
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, scale)
     print(json.dumps(out), flush=True)
 

@@ -68,6 +68,24 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
              int B, int H, int S_q, int S_kv, int D, int causal, float scale,
              void *stream);
 
+/*
+ * attn_fwd_f16 -- the same operation on IEEE fp16 tensors, the element type of the
+ * paper's Section 6 forward-attention evaluation (FP16, HEAD_DIM = 128).
+ *
+ * Arguments, layout, ownership and error behaviour are those of attn_fwd, except:
+ *   q, k, v, o   hold IEEE binary16 instead of bf16; both contractions run on fp16
+ *                MFMA with fp32 accumulation and P is rounded to fp16 (nearest even)
+ *   D            64 or 128 (256 returns ATTN_ERR_UNSUPPORTED_D)
+ *   scale        finite and > 0 (0 returns ATTN_ERR_SCALE)
+ *   S_kv * D     below 2^30 (one head of K addressed with 32-bit byte offsets;
+ *                larger returns ATTN_ERR_SHAPE)
+ * Inputs whose scores or values overflow fp16 range are the caller's concern, as
+ * NaN/Inf are for attn_fwd.
+ */
+int attn_fwd_f16(const void *q, const void *k, const void *v, void *o, float *lse,
+                 int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+                 void *stream);
+
 /* Static, NUL-terminated description of an attn_status value; never freed. */
 const char *attn_strerror(int status);
 

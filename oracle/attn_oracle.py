@@ -6,8 +6,8 @@ softmax bookkeeping that Section 6.2 mentions written out in full; see the
 header of attn_ref.c for the formulas.  Nothing here imports, or is imported
 by, the HIP package.
 
-Inputs are numpy uint16 arrays holding bf16 bit patterns, shaped
-[B, H, S, D]; outputs are numpy float64.
+Inputs are numpy uint16 arrays holding bf16 (default) or IEEE binary16
+bit patterns, shaped [B, H, S, D]; outputs are numpy float64.
 """
 import ctypes
 import os
@@ -36,13 +36,14 @@ def _load():
     global _lib
     if _lib is None:
         lib = ctypes.CDLL(build())
-        lib.attn_ref_f64.restype = ctypes.c_int
-        lib.attn_ref_f64.argtypes = [
-            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-            ctypes.c_int, ctypes.c_float,
-            ctypes.c_int64, ctypes.c_void_p,
-            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        for fn in (lib.attn_ref_f64, lib.attn_ref_f64_f16):
+            fn.restype = ctypes.c_int
+            fn.argtypes = [
+                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                ctypes.c_int, ctypes.c_float,
+                ctypes.c_int64, ctypes.c_void_p,
+                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         lib.attn_ref_max_threads.restype = ctypes.c_int
         lib.attn_ref_max_threads.argtypes = []
         _lib = lib
@@ -53,10 +54,11 @@ def max_threads():
     return int(_load().attn_ref_max_threads())
 
 
-def attn_ref(q, k, v, causal, scale, rows=None, n_threads=0):
+def attn_ref(q, k, v, causal, scale, rows=None, n_threads=0, dtype="bf16"):
     """Oracle attention.
 
-    q: uint16 [B,H,S_q,D]; k, v: uint16 [B,H,S_kv,D] (bf16 bit patterns).
+    q: uint16 [B,H,S_q,D]; k, v: uint16 [B,H,S_kv,D]: bit patterns of `dtype`,
+    "bf16" or "f16" (IEEE binary16).
     scale: rounded to fp32 first (the value the GPU entry point receives).
     rows: None -> every row, returns O [B,H,S_q,D], LSE [B,H,S_q];
           else a 1-D int64 array of flat row ids (b*H + h)*S_q + i,
@@ -68,7 +70,7 @@ def attn_ref(q, k, v, causal, scale, rows=None, n_threads=0):
     v = np.ascontiguousarray(v)
     for a in (q, k, v):
         if a.dtype != np.uint16 or a.ndim != 4:
-            raise TypeError("q, k, v must be uint16 [B,H,S,D] arrays of bf16 bits")
+            raise TypeError("q, k, v must be uint16 [B,H,S,D] arrays of 16-bit patterns")
     B, H, S_q, D = q.shape
     if k.shape != v.shape or k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
         raise ValueError("shape mismatch between q, k, v")
@@ -84,10 +86,13 @@ def attn_ref(q, k, v, causal, scale, rows=None, n_threads=0):
         rows_p = rows.ctypes.data
         o = np.empty((n, D), dtype=np.float64)
         lse = np.empty((n,), dtype=np.float64)
-    rc = lib.attn_ref_f64(q.ctypes.data, k.ctypes.data, v.ctypes.data,
-                          B, H, S_q, S_kv, D, int(bool(causal)),
-                          float(np.float32(scale)), n, rows_p,
-                          o.ctypes.data, lse.ctypes.data, int(n_threads))
+    if dtype not in ("bf16", "f16"):
+        raise ValueError("dtype must be 'bf16' or 'f16'")
+    fn = lib.attn_ref_f64 if dtype == "bf16" else lib.attn_ref_f64_f16
+    rc = fn(q.ctypes.data, k.ctypes.data, v.ctypes.data,
+            B, H, S_q, S_kv, D, int(bool(causal)),
+            float(np.float32(scale)), n, rows_p,
+            o.ctypes.data, lse.ctypes.data, int(n_threads))
     if rc != 0:
         raise RuntimeError("attn_ref_f64 failed (bad argument or out of memory)")
     return o, lse

@@ -23,9 +23,10 @@
  *   LSE_i = m_i + ln(l_i)                             (natural log)
  *   O_id  = (1/l_i) * sum_j exp(s_ij - m_i) * v[b,h,j,d]
  *
- * Everything is IEEE fp64.  Inputs are bf16 bit patterns (uint16) widened
- * exactly; `scale` is the caller's fp32 value widened exactly.  Outputs are
- * fp64 and are not rounded to bf16/fp32.
+ * Everything is IEEE fp64.  Inputs are 16-bit patterns (uint16) widened
+ * exactly: bf16 (attn_ref_f64), or IEEE binary16 (attn_ref_f64_f16), the
+ * element type of the paper's Section 6 evaluation.  `scale` is the caller's
+ * fp32 value widened exactly.  Outputs are fp64 and are not rounded.
  *
  * Layout: q [B][H][S_q][D], k and v [B][H][S_kv][D], contiguous, row-major.
  * Rows are addressed by a flat id  r = (b*H + h)*S_q + i.
@@ -47,10 +48,28 @@ static double bf16_bits_to_f64(uint16_t bits)
     return (double)f;
 }
 
-/* One output row.  `s` is scratch for S_kv doubles. */
+static double f16_bits_to_f64(uint16_t bits)
+{
+    /* IEEE 754 binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits. */
+    const int sign = bits >> 15;
+    const int e = (bits >> 10) & 0x1f;
+    const int f = bits & 0x3ff;
+    double x;
+    if (e == 0)
+        x = ldexp((double)f, -24); /* zero and subnormals: f * 2^-10 * 2^-14 */
+    else if (e == 31)
+        x = f ? NAN : INFINITY;
+    else
+        x = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    return sign ? -x : x;
+}
+
+typedef double (*decode_fn)(uint16_t);
+
+/* One output row.  `s` is scratch for S_kv doubles; `dec` widens one input element. */
 static void attn_row(const uint16_t *q_row, const uint16_t *k_head, const uint16_t *v_head,
                      int64_t i, int S_kv, int D, int causal, double scale,
-                     double *s, double *o_row, double *lse_out)
+                     double *s, double *o_row, double *lse_out, decode_fn dec)
 {
     int64_t n = S_kv;
     if (causal && i + 1 < n)
@@ -62,7 +81,7 @@ static void attn_row(const uint16_t *q_row, const uint16_t *k_head, const uint16
         const uint16_t *k_row = k_head + j * (int64_t)D;
         double dot = 0.0;
         for (int d = 0; d < D; ++d)
-            dot += bf16_bits_to_f64(q_row[d]) * bf16_bits_to_f64(k_row[d]);
+            dot += dec(q_row[d]) * dec(k_row[d]);
         s[j] = scale * dot;
         if (s[j] > m)
             m = s[j];
@@ -77,7 +96,7 @@ static void attn_row(const uint16_t *q_row, const uint16_t *k_head, const uint16
         const uint16_t *v_row = v_head + j * (int64_t)D;
         l += p;
         for (int d = 0; d < D; ++d)
-            o_row[d] += p * bf16_bits_to_f64(v_row[d]);
+            o_row[d] += p * dec(v_row[d]);
     }
     for (int d = 0; d < D; ++d)
         o_row[d] /= l;
@@ -92,10 +111,10 @@ static void attn_row(const uint16_t *q_row, const uint16_t *k_head, const uint16
  *   n_threads <= 0 : OpenMP default
  * returns 0, or -1 on a bad argument / allocation failure.
  */
-int attn_ref_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v,
-                 int B, int H, int S_q, int S_kv, int D, int causal, float scale,
-                 int64_t n_rows, const int64_t *rows,
-                 double *o, double *lse, int n_threads)
+static int attn_ref_any(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                        int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+                        int64_t n_rows, const int64_t *rows,
+                        double *o, double *lse, int n_threads, decode_fn dec)
 {
     if (!q || !k || !v || !o || !lse)
         return -1;
@@ -136,11 +155,30 @@ int attn_ref_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v,
                      k + bh * (int64_t)S_kv * D,
                      v + bh * (int64_t)S_kv * D,
                      i, S_kv, D, causal, scale64,
-                     s, o + t * (int64_t)D, lse + t);
+                     s, o + t * (int64_t)D, lse + t, dec);
         }
         free(s);
     }
     return failed ? -1 : 0;
+}
+
+int attn_ref_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                 int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+                 int64_t n_rows, const int64_t *rows,
+                 double *o, double *lse, int n_threads)
+{
+    return attn_ref_any(q, k, v, B, H, S_q, S_kv, D, causal, scale, n_rows, rows, o, lse, n_threads,
+                        bf16_bits_to_f64);
+}
+
+/* Same, with q, k, v holding IEEE binary16 bit patterns. */
+int attn_ref_f64_f16(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                     int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+                     int64_t n_rows, const int64_t *rows,
+                     double *o, double *lse, int n_threads)
+{
+    return attn_ref_any(q, k, v, B, H, S_q, S_kv, D, causal, scale, n_rows, rows, o, lse, n_threads,
+                        f16_bits_to_f64);
 }
 
 /* Number of threads an n_threads <= 0 call would use (for reporting). */

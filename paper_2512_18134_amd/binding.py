@@ -19,6 +19,8 @@ if not os.path.exists(LIB_PATH):
 _lib = ctypes.CDLL(LIB_PATH)
 _lib.attn_fwd.restype = ctypes.c_int
 _lib.attn_fwd.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
+_lib.attn_fwd_f16.restype = ctypes.c_int
+_lib.attn_fwd_f16.argtypes = _lib.attn_fwd.argtypes
 _lib.attn_strerror.restype = ctypes.c_char_p
 _lib.attn_strerror.argtypes = [ctypes.c_int]
 _lib.attn_version.restype = ctypes.c_int
@@ -53,6 +55,12 @@ def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S_q, S_kv, D, causal
                              int(bool(causal)), float(scale), stream_ptr))
 
 
+def attn_fwd_f16_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S_q, S_kv, D, causal, scale, stream_ptr):
+    """attn_fwd_f16 with raw integer addresses; returns the attn_status."""
+    return int(_lib.attn_fwd_f16(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S_q, S_kv, D,
+                                 int(bool(causal)), float(scale), stream_ptr))
+
+
 def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
     """attn_fwd on torch device tensors.
 
@@ -62,10 +70,21 @@ def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
     Returns (o, lse).
     """
     import torch
+    return _marshal(attn_fwd_raw, torch.bfloat16, q, k, v, o, lse, causal, scale, stream)
+
+
+def attn_fwd_f16(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
+    """attn_fwd_f16 on torch device tensors: as attn_fwd, with fp16 q, k, v, o (D = 64 or 128)."""
+    import torch
+    return _marshal(attn_fwd_f16_raw, torch.float16, q, k, v, o, lse, causal, scale, stream)
+
+
+def _marshal(entry, dt, q, k, v, o, lse, causal, scale, stream):
+    import torch
 
     for t in (q, k, v):
-        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
-            raise TypeError("q, k, v must be contiguous 4-D bf16 tensors on the GPU")
+        if t.dtype != dt or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise TypeError("q, k, v must be contiguous 4-D %s tensors on the GPU" % dt)
     B, H, S_q, D = q.shape
     if k.shape != v.shape or k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
         raise ValueError("q, k, v shapes do not agree")
@@ -74,8 +93,8 @@ def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
         o = torch.empty_like(q)
     if lse is None:
         lse = torch.empty((B, H, S_q), dtype=torch.float32, device=q.device)
-    if o.dtype != torch.bfloat16 or o.shape != q.shape or not o.is_contiguous() or not o.is_cuda:
-        raise TypeError("o must be a contiguous bf16 GPU tensor shaped like q")
+    if o.dtype != dt or o.shape != q.shape or not o.is_contiguous() or not o.is_cuda:
+        raise TypeError("o must be a contiguous GPU tensor shaped and typed like q")
     if lse.dtype != torch.float32 or tuple(lse.shape) != (B, H, S_q) or not lse.is_contiguous() or not lse.is_cuda:
         raise TypeError("lse must be a contiguous fp32 GPU tensor [B,H,S_q]")
     if scale is None:
@@ -83,8 +102,8 @@ def attn_fwd(q, k, v, o=None, lse=None, causal=False, scale=None, stream=None):
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
     with torch.cuda.device(q.device):
-        rc = attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
-                          B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
+        rc = entry(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                   B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
     if rc != ATTN_OK:
         raise AttnError(rc)
     return o, lse

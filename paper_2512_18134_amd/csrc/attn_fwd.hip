@@ -71,6 +71,15 @@ int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_asm_kernel<D, false>, p, BH, 256, 512, LDS, stream);
 }
 
+template <int D>
+int launch_asm_f16(const Params &p, int BH, int causal, hipStream_t stream)
+{
+    constexpr int LDS = 8 * 64 * D * 2;
+    if (causal)
+        return launch(attn::attn_fwd_asm_kernel<D, true, true>, p, BH, 256, 512, LDS, stream);
+    return launch(attn::attn_fwd_asm_kernel<D, false, true>, p, BH, 256, 512, LDS, stream);
+}
+
 template <int D, int QB>
 int launch_asm2(const Params &p, int BH, int causal, hipStream_t stream)
 {
@@ -105,8 +114,9 @@ int launch_pipe_variant(int variant, const Params &p, int BH, int causal, hipStr
 
 }  // namespace
 
-extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
-                        int S_kv, int D, int causal, float scale, void *stream)
+// host-side validation shared by the entry points; fills `p` on success
+static int validate(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q, int S_kv,
+                    int D, float scale, Params &p)
 {
     if (!q || !k || !v || !o || !lse)
         return ATTN_ERR_NULL;
@@ -123,8 +133,6 @@ extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, fl
         return ATTN_ERR_ALIGN;
     if (!(scale >= 0.f) || isinf(scale))
         return ATTN_ERR_SCALE;
-
-    Params p;
     p.q = static_cast<const attn::bf16_t *>(q);
     p.k = static_cast<const attn::bf16_t *>(k);
     p.v = static_cast<const attn::bf16_t *>(v);
@@ -136,6 +144,37 @@ extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, fl
     p.total_wg = 0;
     p.c = scale * 1.44269504088896340736f;
     p.scale = scale;
+    return ATTN_OK;
+}
+
+extern "C" int attn_fwd_f16(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
+                            int S_kv, int D, int causal, float scale, void *stream)
+{
+    Params p;
+    const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    // fp16 runs on the hand-scheduled 8-wave kernel only
+    if (D == 256)
+        return ATTN_ERR_UNSUPPORTED_D;
+    if ((long long)S_kv * D * 2 >= (1LL << 31))
+        return ATTN_ERR_SHAPE;
+    if (!(scale > 0.f))
+        return ATTN_ERR_SCALE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return D == 64 ? launch_asm_f16<64>(p, B * H, causal, st) : launch_asm_f16<128>(p, B * H, causal, st);
+}
+
+extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
+                        int S_kv, int D, int causal, float scale, void *stream)
+{
+    Params p;
+    {
+        const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
+        if (rc != ATTN_OK)
+            return rc;
+    }
+    const long long BH = (long long)B * H;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     // Debug only: ATTN_FWD_KERNEL=simple forces the generic kernel for every shape.
@@ -184,4 +223,4 @@ extern "C" const char *attn_strerror(int status)
     return "unknown attn_status";
 }
 
-extern "C" int attn_version(void) { return 200; }
+extern "C" int attn_version(void) { return 300; }

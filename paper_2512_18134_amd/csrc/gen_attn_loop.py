@@ -35,16 +35,20 @@ Hazards handled by construction (the assembler inserts no wait states):
     replaying the instruction stream (including the reads prefetched for the
     next iteration).
 
-usage: gen_attn_loop.py <D> <out.inc>
+usage: gen_attn_loop.py <D> <out.inc> [bf16|f16]
 """
 import os
 import sys
 
 
 class Gen:
-    def __init__(self, D, NF=4, PFD=3):
-        assert D in (64, 128)
+    def __init__(self, D, NF=4, PFD=3, dtype="bf16"):
+        assert D in (64, 128) and dtype in ("bf16", "f16")
         self.D = D
+        self.dtype = dtype
+        # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
+        self.mfma = "v_mfma_f32_32x32x16_" + dtype
+        self.cvt = "v_cvt_pk_%s_f32" % dtype
         self.KS = D // 16
         self.DB = D // 32
         self.ROWB = 2 * D
@@ -148,10 +152,10 @@ class Gen:
         if kind == "pv":
             kc, db = a, b
             o = self.vr(self.O + 16 * db, 16)
-            return "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (o, f, self.vr(P_prev + 4 * kc, 4), o)
+            return "%s %s, %s, %s, %s" % (self.mfma, o, f, self.vr(P_prev + 4 * kc, 4), o)
         ks, sb = a, b
         s = self.vr(S_nxt + 16 * sb, 16)
-        return "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (s, f, self.vr(self.Q + 4 * ks, 4), "0" if ks == 0 else s)
+        return "%s %s, %s, %s, %s" % (self.mfma, s, f, self.vr(self.Q + 4 * ks, 4), "0" if ks == 0 else s)
 
     # ---------------------------------------------------------- softmax programs
     def max_ops(self, S_cur):
@@ -202,7 +206,7 @@ class Gen:
         def A(k):
             return ["v_add_f32 v%d, v%d, v%d" % (self.LA, self.LA, S_cur + 2 * k),
                     "v_add_f32 v%d, v%d, v%d" % (self.LB, self.LB, S_cur + 2 * k + 1),
-                    "v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (P_new + k, S_cur + 2 * k, S_cur + 2 * k + 1)]
+                    "%s v%d, v%d, v%d" % (self.cvt, P_new + k, S_cur + 2 * k, S_cur + 2 * k + 1)]
         if "novalu" in self.exp:
             return []
         for t in range(16 + 2):
@@ -444,7 +448,7 @@ class Gen:
         self.generate()
         D, DB, KS = self.D, self.DB, self.KS
         out = []
-        out.append("// Generated by gen_attn_loop.py %d -- do not edit.  Main loop of attn_fwd_asm_kernel<%d, *>." % (D, D))
+        out.append("// Generated by gen_attn_loop.py %d %s -- do not edit.  Main loop of attn_fwd_asm_kernel<%d, *> (%s)." % (D, self.dtype, D, self.dtype))
         out.append("// VGPRs used: %d.  MFMA slots per iteration: %d." % (self.NV, self.NM))
         out.append("asm volatile(")
         for ln in self.lines:
@@ -499,6 +503,7 @@ class Gen:
 
 if __name__ == "__main__":
     D = int(sys.argv[1])
-    text = Gen(D, PFD=int(os.environ.get("ATTN_GEN_PFD", "3"))).emit_inc()
+    dtype = sys.argv[3] if len(sys.argv) > 3 else "bf16"
+    text = Gen(D, PFD=int(os.environ.get("ATTN_GEN_PFD", "3")), dtype=dtype).emit_inc()
     with open(sys.argv[2], "w") as f:
         f.write(text)

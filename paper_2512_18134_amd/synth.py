@@ -1,7 +1,8 @@
 """Seeded synthetic Q/K/V for the attention forward path.
 
 This module is shared by the tests, the oracle's callers and the bench.  It
-holds none of the attention arithmetic: it only produces bf16 bit patterns.
+holds none of the attention arithmetic: it only produces 16-bit float bit patterns
+(bf16, or IEEE fp16 with dtype="f16").
 
 The generator is counter based, so every element depends only on
 (seed, tensor id, flat index): generation order, chunking and threading do not
@@ -69,10 +70,21 @@ def bf16_bits_to_f32(bits):
     return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def normal_bf16(seed, tensor_id, shape, row_offset_id=None, row_offset_sigma=0.0, chunk=1 << 22):
-    """bf16 bits of iid N(0,1) values of `shape` ([..., D]); optionally every
-    row (last axis) gets one extra scalar N(0, row_offset_sigma^2) added in
-    fp32 before the rounding to bf16."""
+def f32_to_f16_bits(x):
+    """Round-to-nearest-even fp32 -> IEEE fp16 bit patterns (uint16)."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(bits):
+    """Exact widening of fp16 bit patterns (uint16) to fp32."""
+    return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def normal_bf16(seed, tensor_id, shape, row_offset_id=None, row_offset_sigma=0.0, chunk=1 << 22, dtype="bf16"):
+    """16-bit patterns (bf16, or fp16 with dtype="f16") of iid N(0,1) values of `shape`
+    ([..., D]); optionally every row (last axis) gets one extra scalar
+    N(0, row_offset_sigma^2) added in fp32 before the rounding to 16 bits."""
+    pack = {"bf16": f32_to_bf16_bits, "f16": f32_to_f16_bits}[dtype]
     n = int(np.prod(shape))
     d = int(shape[-1])
     out = np.empty(n, dtype=np.uint16)
@@ -84,7 +96,7 @@ def normal_bf16(seed, tensor_id, shape, row_offset_id=None, row_offset_sigma=0.0
         x = normal_f64(seed, tensor_id, s, c).astype(np.float32)
         if row_offset_id is not None:
             x = (x.reshape(-1, d) + off[s // d:(s + c) // d, None]).reshape(-1)
-        out[s:s + c] = f32_to_bf16_bits(x)
+        out[s:s + c] = pack(x)
     return out.reshape(shape)
 
 
@@ -103,16 +115,24 @@ def default_scale(D):
     return float(np.float32(1.0 / np.sqrt(np.float64(D))))
 
 
-def make_qkv(B, H, S_q, S_kv, D, seed, sharp=False):
-    """(q, k, v) as uint16 bf16-bit arrays, shapes [B,H,S_q,D], [B,H,S_kv,D] x2."""
+def make_qkv(B, H, S_q, S_kv, D, seed, sharp=False, dtype="bf16"):
+    """(q, k, v) as uint16 arrays of `dtype` bits ("bf16" or "f16"), shapes [B,H,S_q,D], [B,H,S_kv,D] x2."""
     if sharp:
-        q = normal_bf16(seed, TENSOR_Q, (B, H, S_q, D), TENSOR_OFFQ, 2.0)
-        k = normal_bf16(seed, TENSOR_K, (B, H, S_kv, D), TENSOR_OFFK, 2.0)
+        q = normal_bf16(seed, TENSOR_Q, (B, H, S_q, D), TENSOR_OFFQ, 2.0, dtype=dtype)
+        k = normal_bf16(seed, TENSOR_K, (B, H, S_kv, D), TENSOR_OFFK, 2.0, dtype=dtype)
     else:
-        q = normal_bf16(seed, TENSOR_Q, (B, H, S_q, D))
-        k = normal_bf16(seed, TENSOR_K, (B, H, S_kv, D))
-    v = normal_bf16(seed, TENSOR_V, (B, H, S_kv, D))
+        q = normal_bf16(seed, TENSOR_Q, (B, H, S_q, D), dtype=dtype)
+        k = normal_bf16(seed, TENSOR_K, (B, H, S_kv, D), dtype=dtype)
+    v = normal_bf16(seed, TENSOR_V, (B, H, S_kv, D), dtype=dtype)
     return q, k, v
+
+
+def paper_workload(seq, causal, D=128, BH=128):
+    """Shape of the paper's Section 6.2 sweep: BATCH * NUM_HEADS = BH heads of HEAD_DIM = 128, fp16
+    N(0,1) inputs, `seq` queries and keys; the figure's x axis is `seq` (1k .. 16k)."""
+    return dict(name="paper_B%d_H32_S%d_D%d_%s_f16" % (BH // 32, seq, D, "causal" if causal else "full"),
+                B=BH // 32, H=32, S_q=seq, S_kv=seq, D=D, causal=bool(causal), seed=100 + seq // 1024,
+                sharp=False, dtype="f16")
 
 
 def make_config(index):

@@ -25,7 +25,7 @@ def declared_symbols():
 
 def test_header_symbols_are_exported(binding):
     names = declared_symbols()
-    assert {"attn_fwd", "attn_strerror", "attn_version"} <= set(names)
+    assert {"attn_fwd", "attn_fwd_f16", "attn_strerror", "attn_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), "symbol %s missing from libmi355attn.so" % n
@@ -58,6 +58,24 @@ def test_validation_happens_before_any_launch(binding):
     assert f(lse=ok + 2) == b.ATTN_ERR_ALIGN
     for s in (float("nan"), float("inf"), -1.0):
         assert f(scale=s) == b.ATTN_ERR_SCALE
+
+
+def test_f16_entry_validates_like_the_bf16_one_and_narrows_d_and_scale(binding):
+    b = binding
+    ok = 0x1000
+    f = lambda **kw: b.attn_fwd_f16_raw(*[kw.get(n, d) for n, d in (
+        ("q", ok), ("k", ok), ("v", ok), ("o", ok), ("lse", ok), ("B", 1), ("H", 1), ("S_q", 8), ("S_kv", 8),
+        ("D", 64), ("causal", 0), ("scale", 0.125), ("stream", 0))])
+    for name in ("q", "k", "v", "o", "lse"):
+        assert f(**{name: 0}) == b.ATTN_ERR_NULL
+    for name in ("B", "H", "S_q", "S_kv"):
+        assert f(**{name: 0}) == b.ATTN_ERR_SHAPE
+    for D in (0, 32, 96, 256, 512):
+        assert f(D=D) == b.ATTN_ERR_UNSUPPORTED_D
+    assert f(q=ok + 8) == b.ATTN_ERR_ALIGN
+    for s in (float("nan"), float("inf"), -1.0, 0.0):
+        assert f(scale=s) == b.ATTN_ERR_SCALE
+    assert f(S_kv=1 << 24, D=128) == b.ATTN_ERR_SHAPE  # one head of K beyond 32-bit byte offsets
 
 
 def test_product_package_does_not_import_the_oracle():

@@ -223,6 +223,60 @@ def test_against_torch_cpu_fp64(shape, causal):
     assert np.max(np.abs(lse - want_l)) < 1e-12
 
 
+# ------------------------------------------------------------ fp16 inputs (Section 6's element type)
+def test_f16_decoding_of_every_finite_pattern():
+    # one key: the softmax weight is 1, so O is the value row itself and LSE = scale * q.k;
+    # numpy's float16 is the independent IEEE binary16 decoder (subnormals included)
+    bits = np.arange(65536, dtype=np.uint16)
+    bits = bits[np.isfinite(bits.view(np.float16))]
+    n = bits.size
+    assert n == 63488
+    want = bits.view(np.float16).astype(np.float64)
+    one = np.array([0x3C00], dtype=np.uint16)  # 1.0
+    # V: [n heads][1 key][1]; Q = K = 1
+    v = bits.reshape(1, n, 1, 1)
+    qk = np.broadcast_to(one, (1, n, 1, 1)).copy()
+    o, lse = attn_ref(qk, qk, v, False, 1.0, dtype="f16")
+    assert np.array_equal(o.reshape(-1), want)   # (-0 compares equal to the accumulated +0)
+    assert np.array_equal(lse.reshape(-1), np.ones(n))
+    # Q, then K, run over every pattern against a unit partner: LSE = the decoded value
+    for which in (0, 1):
+        q = bits.reshape(1, n, 1, 1) if which == 0 else qk
+        k = qk if which == 0 else bits.reshape(1, n, 1, 1)
+        _, lse = attn_ref(q, k, qk, False, 1.0, dtype="f16")
+        assert np.array_equal(lse.reshape(-1), want + 0.0)
+    # the same bits read as bf16 give other numbers: the dtype switch is live
+    _, lse_b = attn_ref(bits.reshape(1, n, 1, 1), qk, qk, False, 1.0, dtype="bf16")
+    assert not np.array_equal(lse_b.reshape(-1), want)
+
+
+def test_f16_two_key_logistic_with_a_value_bf16_cannot_hold():
+    x = 1.0 + 2.0 ** -10          # exact in fp16, not in bf16
+    f16 = lambda a: np.asarray(a, dtype=np.float16).view(np.uint16)
+    q = f16([[[[x, 0.0]]]])
+    k = f16([[[[1.0, 0.0], [0.0, 0.0]]]])
+    v = f16([[[[1.0, 0.0], [0.0, 1.0]]]])
+    o, lse = attn_ref(q, k, v, False, 1.0, dtype="f16")
+    w = 1.0 / (1.0 + math.exp(-x))
+    assert abs(o[0, 0, 0, 0] - w) < 1e-15 and abs(o[0, 0, 0, 1] - (1 - w)) < 1e-15
+    assert abs(lse[0, 0, 0] - math.log(math.exp(x) + 1.0)) < 1e-15
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_f16_against_torch_cpu_fp64(causal):
+    B, H, Sq, Skv, D = 1, 2, 50, 90, 128
+    q, k, v = synth.make_qkv(B, H, Sq, Skv, D, 77, dtype="f16")
+    scale = synth.default_scale(D)
+    o, lse = attn_ref(q, k, v, causal, scale, dtype="f16")
+    qt, kt, vt = (torch.from_numpy(x.view(np.float16).astype(np.float64)) for x in (q, k, v))
+    s = torch.matmul(qt, kt.transpose(-1, -2)) * scale
+    if causal:
+        keep = torch.arange(Skv)[None, :] <= torch.arange(Sq)[:, None]
+        s = s.masked_fill(~keep, float("-inf"))
+    assert np.max(np.abs(o - torch.matmul(torch.softmax(s, dim=-1), vt).numpy())) < 1e-12
+    assert np.max(np.abs(lse - torch.logsumexp(s, dim=-1).numpy())) < 1e-12
+
+
 def test_lse_brute_force_long_double():
     # small scores: log(sum(exp(s))) needs no max shift; do it in long double
     q, k, v = rand_qkv(30, 1, 1, 6, 11, 4)

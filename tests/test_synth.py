@@ -41,6 +41,22 @@ def test_bf16_rne():
     assert np.array_equal(synth.f32_to_bf16_bits(f[fin]), allbits[fin])
 
 
+def test_f16_generation_is_the_same_normals_rounded_to_half():
+    shape = (1, 2, 33, 64)
+    b = synth.make_qkv(1, 2, 33, 33, 64, 5)[0]
+    h = synth.make_qkv(1, 2, 33, 33, 64, 5, dtype="f16")[0]
+    assert h.dtype == np.uint16 and h.shape == shape
+    x = synth.normal_f64(5, synth.TENSOR_Q, 0, int(np.prod(shape))).astype(np.float32).reshape(shape)
+    assert np.array_equal(h.view(np.float16), x.astype(np.float16))
+    # fp16 keeps 3 more fraction bits than bf16 for |x| in normal range
+    eb = np.abs(synth.bf16_bits_to_f32(b) - x).max()
+    eh = np.abs(synth.f16_bits_to_f32(h) - x).max()
+    assert eh < eb / 4
+    assert np.array_equal(synth.f32_to_f16_bits(synth.f16_bits_to_f32(h)), h)
+    w = synth.paper_workload(16384, False)
+    assert (w["B"], w["H"], w["S_q"], w["S_kv"], w["D"], w["causal"], w["dtype"]) == (4, 32, 16384, 16384, 128, False, "f16")
+
+
 def test_sharp_rows_have_offsets():
     q, k, v = synth.make_qkv(1, 2, 64, 64, 256, seed=4, sharp=True)
     qf = synth.bf16_bits_to_f32(q)
