@@ -63,4 +63,31 @@ struct Params {
     float scale;
 };
 
+// Workgroup id -> (batch*head, query tile).
+//  * not causal: all tiles cost the same; every XCD takes a contiguous range of (bh, qt) pairs.
+//  * causal: query tile qt streams ~(qt + 1) times as many K/V tiles as tile 0, and a CU holds one
+//    workgroup at a time, so the dispatch order decides the balance: each XCD hands out its tiles
+//    heaviest first ACROSS its heads (a CU that finishes a light tile of the first batch then picks up
+//    the heaviest one left).  With B*H a multiple of the XCD count every XCD owns whole heads (K/V stay
+//    in one L2); otherwise the order is heaviest-first over the whole grid.
+template <bool CAUSAL>
+__device__ __forceinline__ void wg_to_tile(int wid, const Params &p, int &bh, int &qt)
+{
+    if (!CAUSAL) {
+        const int logical = xcd_remap(wid, p.total_wg);
+        bh = logical / p.n_qt;
+        qt = logical % p.n_qt;
+        return;
+    }
+    const int n_bh = p.total_wg / p.n_qt;
+    if (n_bh % kNumXcd == 0) {
+        const int nh = n_bh / kNumXcd, xcd = wid % kNumXcd, i = wid / kNumXcd;
+        qt = p.n_qt - 1 - i / nh;
+        bh = xcd * nh + i % nh;
+    } else {
+        qt = p.n_qt - 1 - wid / n_bh;
+        bh = wid % n_bh;
+    }
+}
+
 }  // namespace attn

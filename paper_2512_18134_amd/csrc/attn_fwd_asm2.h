@@ -50,11 +50,8 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
     const int lq = lane & 31;
     const int g = lane >> 5;
 
-    const int logical = xcd_remap(blockIdx.x, p.total_wg);
-    const int bh = logical / p.n_qt;
-    int qt = logical % p.n_qt;
-    if (CAUSAL)
-        qt = p.n_qt - 1 - qt;
+    int bh, qt;
+    wg_to_tile<CAUSAL>(blockIdx.x, p, bh, qt);
     const int q0 = qt * BM;
     auto qcol = [&](int qb) { return q0 + (wave * QB + qb) * 32 + lq; };
 

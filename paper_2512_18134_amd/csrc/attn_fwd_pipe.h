@@ -96,11 +96,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pipe_kernel(const Params p)
     const int lq = lane & 31;
     const int g = lane >> 5;
 
-    const int logical = xcd_remap(blockIdx.x, p.total_wg);
-    const int bh = logical / p.n_qt;
-    int qt = logical % p.n_qt;
-    if (CAUSAL)
-        qt = p.n_qt - 1 - qt;
+    int bh, qt;
+    wg_to_tile<CAUSAL>(blockIdx.x, p, bh, qt);
     const int q0 = qt * BM;
     const int q0w = q0 + wave * 32 * QB;
     auto qcol = [&](int qb) { return q0w + 32 * qb + lq; };  // query row of this lane in block qb

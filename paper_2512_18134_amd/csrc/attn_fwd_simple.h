@@ -38,11 +38,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_simple_kernel(const Params p
     const int g = lane >> 5;   // which half of the keys of a 32-key block
 
     // ---- workgroup -> (b*H+h, query tile), XCD-aware, heaviest causal tiles first
-    const int logical = xcd_remap(blockIdx.x, p.total_wg);
-    const int bh = logical / p.n_qt;
-    int qt = logical % p.n_qt;
-    if (CAUSAL)
-        qt = p.n_qt - 1 - qt;
+    int bh, qt;
+    wg_to_tile<CAUSAL>(blockIdx.x, p, bh, qt);
 
     const int q0 = qt * BM;
     const int q0w = q0 + wave * 32;
