@@ -26,7 +26,7 @@ _GOLD = np.uint64(0x9E3779B97F4A7C15)
 _C1 = np.uint64(0xBF58476D1CE4E5B9)
 _C2 = np.uint64(0x94D049BB133111EB)
 
-TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_OFFQ, TENSOR_OFFK = 0, 1, 2, 3, 4
+TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_OFFQ, TENSOR_OFFK, TENSOR_DO = 0, 1, 2, 3, 4, 5
 
 
 def _splitmix64(x):
@@ -125,6 +125,11 @@ def make_qkv(B, H, S_q, S_kv, D, seed, sharp=False, dtype="bf16"):
         k = normal_bf16(seed, TENSOR_K, (B, H, S_kv, D), dtype=dtype)
     v = normal_bf16(seed, TENSOR_V, (B, H, S_kv, D), dtype=dtype)
     return q, k, v
+
+
+def make_do(B, H, S_q, D, seed, dtype="bf16"):
+    """Upstream gradient dO for the backward pass: iid N(0,1), same generator, its own tensor id."""
+    return normal_bf16(seed, TENSOR_DO, (B, H, S_q, D), dtype=dtype)
 
 
 def paper_workload(seq, causal, D=128, BH=128):
