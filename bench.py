@@ -62,6 +62,49 @@ def cpu_baseline(cfg, q, k, v, scale, target_seconds=15.0):
             "sample": "%d of %d rows (uniform random, seed 1234), %.1f s wall, fp64 two-pass oracle, OpenMP" % (n, total_rows, dt)}
 
 
+def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops):
+    """One step = one attn_bwd call (Delta kernel, key-owner sweep, query-owner sweep).  Algorithmic work:
+    the five products of the backward pass = 2.5x the forward FLOP (the library computes seven)."""
+    import torch
+    from paper_2512_18134_amd import binding
+
+    gen = torch.Generator(device=qd.device)
+    gen.manual_seed(cfg["seed"] + 1000)
+    d_o = torch.randn(qd.shape, generator=gen, device=qd.device, dtype=torch.float32).to(qd.dtype)
+    o, lse = binding.attn_fwd(qd, kd, vd, causal=cfg["causal"], scale=scale, stream=stream)
+    dq, dk, dv = torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd)
+    ws = torch.empty(qd.shape[:3], dtype=torch.float32, device=qd.device)
+    step = lambda: binding.attn_bwd(qd, kd, vd, o, d_o, lse, dq, dk, dv, ws, causal=cfg["causal"], scale=scale,
+                                    stream=stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record(stream)
+        step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+    flops = 2.5 * fwd_flops
+    ms_per_step = wall * 1e3 / args.steps
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (float(np.mean(kern_ms)) * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "attention bwd TFLOP/s at 1 GPU (bf16, D=%d, S=%d, %s)" % (cfg["D"], cfg["S_q"], "causal" if cfg["causal"] else "non-causal"),
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg["name"] + "_bwd", "B": cfg["B"], "H": cfg["H"], "S_q": cfg["S_q"], "S_kv": cfg["S_kv"],
+                   "D": cfg["D"], "causal": cfg["causal"], "flop_per_step": flops,
+                   "kernel_ms_avg": float(np.mean(kern_ms)), "kernel_ms_min": float(np.min(kern_ms))},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,6 +115,8 @@ def main():
                     help="time the paper's Section 6.2 shape (B=4, H=32, D=128, non-causal) at this sequence length")
     ap.add_argument("--dtype", choices=["bf16", "f16"], default=None,
                     help="element type (default: bf16 for --config, f16 for --paper-seq)")
+    ap.add_argument("--bwd", action="store_true",
+                    help="time the backward pass (attn_bwd: Delta kernel + two sweeps) instead; bf16 only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB device copy instead (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -125,6 +170,11 @@ def main():
     flops = synth.attention_flops(cfg["B"], cfg["H"], cfg["S_q"], cfg["S_kv"], cfg["D"], cfg["causal"])
 
     stream = torch.cuda.current_stream(dev)
+    if args.bwd:
+        if cfg["dtype"] != "bf16":
+            print("bench.py: --bwd runs in bf16 (use --dtype bf16 with --paper-seq)", file=sys.stderr)
+            sys.exit(2)
+        return bench_bwd(args, cfg, qd, kd, vd, scale, stream, flops)
     step = lambda: entry(qd, kd, vd, o, lse, causal=cfg["causal"], scale=scale, stream=stream)
     for _ in range(args.warmup):
         step()

@@ -21,6 +21,8 @@ _lib.attn_fwd.restype = ctypes.c_int
 _lib.attn_fwd.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
 _lib.attn_fwd_f16.restype = ctypes.c_int
 _lib.attn_fwd_f16.argtypes = _lib.attn_fwd.argtypes
+_lib.attn_bwd.restype = ctypes.c_int
+_lib.attn_bwd.argtypes = [ctypes.c_void_p] * 10 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
 _lib.attn_strerror.restype = ctypes.c_char_p
 _lib.attn_strerror.argtypes = [ctypes.c_int]
 _lib.attn_version.restype = ctypes.c_int
@@ -107,3 +109,55 @@ def _marshal(entry, dt, q, k, v, o, lse, causal, scale, stream):
     if rc != ATTN_OK:
         raise AttnError(rc)
     return o, lse
+
+
+def attn_bwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr, dv_ptr, ws_ptr,
+                 B, H, S_q, S_kv, D, causal, scale, stream_ptr):
+    """The C entry point attn_bwd with raw integer addresses; returns the attn_status."""
+    return int(_lib.attn_bwd(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr, dv_ptr, ws_ptr,
+                             B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
+
+
+def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, causal=False, scale=None, stream=None):
+    """attn_bwd on torch device tensors (include/attn_bwd.h).
+
+    q, o, d_o [B,H,S_q,D], k, v [B,H,S_kv,D]: contiguous bf16 on the GPU; lse fp32 [B,H,S_q] as
+    written by attn_fwd.  dq, dk, dv (bf16) and the fp32 workspace delta_ws [B,H,S_q] are
+    allocated when not given.  Asynchronous on `stream`.  Returns (dq, dk, dv).
+    """
+    import torch
+
+    dt = torch.bfloat16
+    for t in (q, k, v, o, d_o):
+        if t.dtype != dt or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise TypeError("q, k, v, o, d_o must be contiguous 4-D bf16 tensors on the GPU")
+    B, H, S_q, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
+        raise ValueError("q, k, v shapes do not agree")
+    if o.shape != q.shape or d_o.shape != q.shape:
+        raise ValueError("o and d_o must be shaped like q")
+    S_kv = k.shape[2]
+    if lse.dtype != torch.float32 or tuple(lse.shape) != (B, H, S_q) or not lse.is_contiguous() or not lse.is_cuda:
+        raise TypeError("lse must be a contiguous fp32 GPU tensor [B,H,S_q]")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    if delta_ws is None:
+        delta_ws = torch.empty((B, H, S_q), dtype=torch.float32, device=q.device)
+    for t, like in ((dq, q), (dk, k), (dv, v)):
+        if t.dtype != dt or t.shape != like.shape or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError("dq, dk, dv must be contiguous bf16 GPU tensors shaped like q, k, v")
+    if (delta_ws.dtype != torch.float32 or delta_ws.numel() < B * H * S_q or not delta_ws.is_contiguous()
+            or not delta_ws.is_cuda):
+        raise TypeError("delta_ws must be a contiguous fp32 GPU tensor with at least B*H*S_q elements")
+    if scale is None:
+        scale = 1.0 / float(D) ** 0.5
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    with torch.cuda.device(q.device):
+        rc = attn_bwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
+                          dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), delta_ws.data_ptr(),
+                          B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
+    if rc != ATTN_OK:
+        raise AttnError(rc)
+    return dq, dk, dv

@@ -8,7 +8,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "attn_fwd.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "attn_fwd.hip"), os.path.join(HERE, "csrc", "attn_bwd.hip")]
 LIB_PATH = os.environ.get("ATTN_FWD_LIB_OUT", os.path.join(HERE, "libmi355attn.so"))  # override: experiments only
 
 HIPCC_FLAGS = [

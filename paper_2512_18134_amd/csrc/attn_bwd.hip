@@ -1,0 +1,96 @@
+// attn_bwd.hip -- C ABI entry point attn_bwd (see include/attn_bwd.h): validation and launches.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "attn_bwd.h"  // the C declaration (include/)
+#include "attn_bwd_kernels.h"
+#include "attn_fwd.h"  // attn_status
+
+namespace {
+
+using attn::BwdParams;
+
+template <typename K>
+int launch_sweep(K kern, BwdParams p, int BH, int S_own, int lds_bytes, hipStream_t stream)
+{
+    p.n_t = (S_own + 127) / 128;
+    const long long total = (long long)BH * p.n_t;
+    if (total > 0x7fffffffLL)
+        return ATTN_ERR_SHAPE;
+    p.total_wg = (int)total;
+    if (lds_bytes > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            lds_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return ATTN_ERR_LAUNCH;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(256), lds_bytes, stream, p);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+template <int D>
+int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
+{
+    constexpr int LDS = 2 * 3 * 64 * D * 2 + 3 * 1024;
+    {
+        const long long blocks = (p.n_rows + (256 / (D / 8)) - 1) / (256 / (D / 8));
+        const unsigned grid = (unsigned)(blocks < 4096 ? blocks : 4096);
+        hipLaunchKernelGGL(attn::attn_bwd_delta_kernel<D>, dim3(grid), dim3(256), 0, stream, p);
+        if (hipGetLastError() != hipSuccess)
+            return ATTN_ERR_LAUNCH;
+    }
+    int rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true>, p, BH, p.S_kv, LDS, stream)
+                    : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true>, p, BH, p.S_kv, LDS, stream);
+    if (rc != ATTN_OK)
+        return rc;
+    return causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, false>, p, BH, p.S_q, LDS, stream)
+                  : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, false>, p, BH, p.S_q, LDS, stream);
+}
+
+}  // namespace
+
+extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
+                        void *dq, void *dk, void *dv, float *delta_ws, int B, int H, int S_q, int S_kv, int D,
+                        int causal, float scale, void *stream)
+{
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !delta_ws)
+        return ATTN_ERR_NULL;
+    if (B < 1 || H < 1 || S_q < 1 || S_kv < 1)
+        return ATTN_ERR_SHAPE;
+    if (D != 64 && D != 128)
+        return ATTN_ERR_UNSUPPORTED_D;
+    const long long BH = (long long)B * H;
+    if (BH > 0x7fffffffLL || BH * (long long)(S_q > S_kv ? S_q : S_kv) > (1LL << 40) / D)
+        return ATTN_ERR_SHAPE;
+    // one head of any tensor is addressed with 32-bit byte offsets
+    if ((long long)(S_q > S_kv ? S_q : S_kv) * D * 2 >= (1LL << 31))
+        return ATTN_ERR_SHAPE;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)d_o | (uintptr_t)dq | (uintptr_t)dk |
+         (uintptr_t)dv) & 15)
+        return ATTN_ERR_ALIGN;
+    if (((uintptr_t)lse | (uintptr_t)delta_ws) & 3)
+        return ATTN_ERR_ALIGN;
+    if (!(scale >= 0.f) || isinf(scale))
+        return ATTN_ERR_SCALE;
+    BwdParams p;
+    p.q = static_cast<const attn::bf16_t *>(q);
+    p.k = static_cast<const attn::bf16_t *>(k);
+    p.v = static_cast<const attn::bf16_t *>(v);
+    p.o = static_cast<const attn::bf16_t *>(o);
+    p.d_o = static_cast<const attn::bf16_t *>(d_o);
+    p.lse = lse;
+    p.delta = delta_ws;
+    p.dq = static_cast<attn::bf16_t *>(dq);
+    p.dk = static_cast<attn::bf16_t *>(dk);
+    p.dv = static_cast<attn::bf16_t *>(dv);
+    p.S_q = S_q;
+    p.S_kv = S_kv;
+    p.n_t = 0;
+    p.total_wg = 0;
+    p.n_rows = BH * S_q;
+    p.c = scale * 1.44269504088896340736f;
+    p.scale = scale;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return D == 64 ? launch_bwd<64>(p, (int)BH, causal, st) : launch_bwd<128>(p, (int)BH, causal, st);
+}

@@ -12,6 +12,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
@@ -71,23 +72,29 @@ struct Params {
 //    the heaviest one left).  With B*H a multiple of the XCD count every XCD owns whole heads (K/V stay
 //    in one L2); otherwise the order is heaviest-first over the whole grid.
 template <bool CAUSAL>
-__device__ __forceinline__ void wg_to_tile(int wid, const Params &p, int &bh, int &qt)
+__device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int n_t, int &bh, int &t)
 {
     if (!CAUSAL) {
-        const int logical = xcd_remap(wid, p.total_wg);
-        bh = logical / p.n_qt;
-        qt = logical % p.n_qt;
+        const int logical = xcd_remap(wid, total_wg);
+        bh = logical / n_t;
+        t = logical % n_t;
         return;
     }
-    const int n_bh = p.total_wg / p.n_qt;
+    const int n_bh = total_wg / n_t;
     if (n_bh % kNumXcd == 0) {
         const int nh = n_bh / kNumXcd, xcd = wid % kNumXcd, i = wid / kNumXcd;
-        qt = p.n_qt - 1 - i / nh;
+        t = n_t - 1 - i / nh;
         bh = xcd * nh + i % nh;
     } else {
-        qt = p.n_qt - 1 - wid / n_bh;
+        t = n_t - 1 - wid / n_bh;
         bh = wid % n_bh;
     }
+}
+
+template <bool CAUSAL>
+__device__ __forceinline__ void wg_to_tile(int wid, const Params &p, int &bh, int &qt)
+{
+    wg_to_tile_n<CAUSAL>(wid, p.total_wg, p.n_qt, bh, qt);
 }
 
 }  // namespace attn

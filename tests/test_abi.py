@@ -8,7 +8,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "attn_fwd.h")
+INCLUDE = os.path.join(ROOT, "include")
 
 
 @pytest.fixture(scope="module")
@@ -18,14 +18,17 @@ def binding():
 
 
 def declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(attn_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for fn in sorted(os.listdir(INCLUDE)):
+        if fn.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(INCLUDE, fn)).read(), flags=re.S)
+            names.update(re.findall(r"\b(attn_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(binding):
     names = declared_symbols()
-    assert {"attn_fwd", "attn_fwd_f16", "attn_strerror", "attn_version"} <= set(names)
+    assert {"attn_fwd", "attn_fwd_f16", "attn_bwd", "attn_strerror", "attn_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), "symbol %s missing from libmi355attn.so" % n
@@ -78,6 +81,29 @@ def test_f16_entry_validates_like_the_bf16_one_and_narrows_d_and_scale(binding):
     assert f(S_kv=1 << 24, D=128) == b.ATTN_ERR_SHAPE  # one head of K beyond 32-bit byte offsets
 
 
+def test_bwd_entry_validates_before_any_launch(binding):
+    b = binding
+    ok = 0x1000
+    names = ("q", "k", "v", "o", "d_o", "lse", "dq", "dk", "dv", "ws")
+    def f(**kw):
+        ptrs = [kw.get(n, ok) for n in names]
+        rest = [kw.get(n, d) for n, d in (("B", 1), ("H", 1), ("S_q", 8), ("S_kv", 8), ("D", 64), ("causal", 0),
+                                           ("scale", 0.125), ("stream", 0))]
+        return b.attn_bwd_raw(*(ptrs + rest))
+    for n in names:
+        assert f(**{n: 0}) == b.ATTN_ERR_NULL
+    for n in ("B", "H", "S_q", "S_kv"):
+        assert f(**{n: 0}) == b.ATTN_ERR_SHAPE
+    for D in (0, 32, 96, 256):
+        assert f(D=D) == b.ATTN_ERR_UNSUPPORTED_D
+    for n in ("q", "k", "v", "o", "d_o", "dq", "dk", "dv"):
+        assert f(**{n: ok + 8}) == b.ATTN_ERR_ALIGN
+    assert f(lse=ok + 2) == b.ATTN_ERR_ALIGN and f(ws=ok + 2) == b.ATTN_ERR_ALIGN
+    for s in (float("nan"), float("inf"), -1.0):
+        assert f(scale=s) == b.ATTN_ERR_SCALE
+    assert f(S_q=1 << 24, D=128) == b.ATTN_ERR_SHAPE
+
+
 def test_product_package_does_not_import_the_oracle():
     # the HIP path and the oracle share nothing and neither imports the other
     pkg = os.path.join(ROOT, "paper_2512_18134_amd")
@@ -85,8 +111,8 @@ def test_product_package_does_not_import_the_oracle():
         for fn in files:
             if fn.endswith((".py", ".hip", ".h", ".hpp", ".cpp")):
                 text = open(os.path.join(dirpath, fn)).read()
-                assert not re.search(r"^\s*(from|import)\s+oracle|attn_ref|libattn_ref", text, flags=re.M), fn
+                assert not re.search(r"^\s*(from|import)\s+oracle|attn_ref|attn_bwd_ref|libattn_ref", text, flags=re.M), fn
     for fn in os.listdir(os.path.join(ROOT, "oracle")):
         if fn.endswith((".py", ".c", ".h")):
             text = open(os.path.join(ROOT, "oracle", fn)).read()
-            assert "paper_2512_18134_amd" not in text and "attn_fwd.h" not in text, fn
+            assert "paper_2512_18134_amd" not in text and "attn_fwd.h" not in text and "attn_bwd.h" not in text, fn
