@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "attn_bwd.h"  // the C declaration (include/)
 #include "attn_bwd_kernels.h"
@@ -12,9 +13,9 @@ namespace {
 using attn::BwdParams;
 
 template <typename K>
-int launch_sweep(K kern, BwdParams p, int BH, int S_own, int lds_bytes, hipStream_t stream)
+int launch_sweep(K kern, BwdParams p, int BH, int S_own, int NW, int lds_bytes, hipStream_t stream)
 {
-    p.n_t = (S_own + 127) / 128;
+    p.n_t = (S_own + NW * 32 - 1) / (NW * 32);
     const long long total = (long long)BH * p.n_t;
     if (total > 0x7fffffffLL)
         return ATTN_ERR_SHAPE;
@@ -25,14 +26,15 @@ int launch_sweep(K kern, BwdParams p, int BH, int S_own, int lds_bytes, hipStrea
         (void)hipGetLastError();
         return ATTN_ERR_LAUNCH;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(256), lds_bytes, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(NW * 64), lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
-template <int D>
+template <int D, int QNW>
 int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
 {
-    constexpr int LDS = 2 * 3 * 64 * D * 2 + 3 * 1024;
+    constexpr int NWK = 4, NWQ = QNW;  // waves per workgroup of the key-owner / query-owner sweep
+    constexpr int LDSK = 2 * 3 * 64 * D * 2 + 3 * NWK * 256, LDSQ = 2 * 3 * 64 * D * 2 + 3 * NWQ * 256;
     {
         const long long blocks = (p.n_rows + (256 / (D / 8)) - 1) / (256 / (D / 8));
         const unsigned grid = (unsigned)(blocks < 4096 ? blocks : 4096);
@@ -40,12 +42,12 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
         if (hipGetLastError() != hipSuccess)
             return ATTN_ERR_LAUNCH;
     }
-    int rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true>, p, BH, p.S_kv, LDS, stream)
-                    : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true>, p, BH, p.S_kv, LDS, stream);
+    int rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream)
+                    : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream);
     if (rc != ATTN_OK)
         return rc;
-    return causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, false>, p, BH, p.S_q, LDS, stream)
-                  : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, false>, p, BH, p.S_q, LDS, stream);
+    return causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream)
+                  : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream);
 }
 
 }  // namespace
@@ -92,5 +94,12 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     p.c = scale * 1.44269504088896340736f;
     p.scale = scale;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    return D == 64 ? launch_bwd<64>(p, (int)BH, causal, st) : launch_bwd<128>(p, (int)BH, causal, st);
+    // Debug only: ATTN_BWD_QNW=4 runs the query-owner sweep with one wave per SIMD.
+    static const int qnw = [] {
+        const char *e = getenv("ATTN_BWD_QNW");
+        return e ? atoi(e) : 8;
+    }();
+    if (qnw == 4)
+        return D == 64 ? launch_bwd<64, 4>(p, (int)BH, causal, st) : launch_bwd<128, 4>(p, (int)BH, causal, st);
+    return D == 64 ? launch_bwd<64, 8>(p, (int)BH, causal, st) : launch_bwd<128, 8>(p, (int)BH, causal, st);
 }

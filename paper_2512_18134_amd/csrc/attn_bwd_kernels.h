@@ -23,6 +23,8 @@
 // Streamed tiles (64 rows) arrive by direct global->LDS loads, three ring stages, one
 // barrier per tile.  Instruction scheduling inside a tile is left to the compiler.
 #pragma once
+#include <type_traits>
+
 #include "attn_common.h"
 #include "attn_fwd_pipe.h"  // dma16, wait_vmcnt
 
@@ -73,11 +75,14 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p)
     }
 }
 
-template <int D, bool CAUSAL, bool KEY_OWNER>
-__global__ __launch_bounds__(256) void attn_bwd_sweep_kernel(const BwdParams p)
+// NW = waves per workgroup: 4 (one per SIMD, up to 512 registers: the key-owner sweep needs them) or
+// 8 (two per SIMD, 256 registers: the query-owner sweep fits, and the second wave hides latencies).
+template <int D, bool CAUSAL, bool KEY_OWNER, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_sweep_kernel(const BwdParams p)
 {
     static_assert(D == 64 || D == 128, "backward sweeps: D = 64 or 128");
-    constexpr int BN = 64, NW = 4, BO = NW * 32, NST = 3;
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves: one or two per SIMD");
+    constexpr int BN = 64, BO = NW * 32, NST = 3;
     constexpr int CPR = D / 8;
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
@@ -88,7 +93,7 @@ __global__ __launch_bounds__(256) void attn_bwd_sweep_kernel(const BwdParams p)
     constexpr int NGRP = 2 * NLD + (KEY_OWNER ? 1 : 0);  // direct loads per wave and streamed tile
     constexpr float kLog2e = 1.44269504088896340736f;
 
-    // T1 ring [3][TB] (K, or Q), T2 ring [3][TB] (V, or dO), aux ring [3][4][64] floats (LSE, Delta rows)
+    // T1 ring [3][TB] (K, or Q), T2 ring [3][TB] (V, or dO), aux ring [3][NW][64] floats (LSE, Delta rows)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr uint32_t RING1 = 0, RING2 = NST * TB, AUX = 2 * NST * TB;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(ATTN_LDS_PTR(unsigned char))smem;
@@ -152,10 +157,10 @@ __global__ __launch_bounds__(256) void attn_bwd_sweep_kernel(const BwdParams p)
             dma16(lds0 + RING2 + stage * TB + (i * NW + wave) * 1024, t2, voff);
         }
         if (KEY_OWNER) {
-            // wave 0: LSE of the tile's 64 queries, wave 1: Delta; waves 2, 3 fill spare slots so that
+            // even waves: LSE of the tile's 64 queries, odd waves: Delta; waves past the first two fill spare slots so that
             // every wave has the same number of loads in flight
             const int r = min(t * BN + lane, p.S_q - 1);
-            dma4(lds0 + AUX + (stage * 4 + wave) * 256, (wave & 1) ? delta_head : lse_head, (uint32_t)r * 4);
+            dma4(lds0 + AUX + (stage * NW + wave) * 256, (wave & 1) ? delta_head : lse_head, (uint32_t)r * 4);
         }
     };
 
@@ -226,8 +231,117 @@ __global__ __launch_bounds__(256) void attn_bwd_sweep_kernel(const BwdParams p)
             acc2[db][r] = 0.f;
         }
 
-    for (int t = t_begin; t < t_end; ++t) {
-        const int st = (t - t_begin) % NST;
+    // Streamed tiles.  With two waves per SIMD the loop is unrolled by the ring depth so that the stage
+    // offsets of the LDS reads are instruction immediates; with one wave per SIMD the rolled loop
+    // (stage offset in a register) is what the compiler schedules best.
+    if constexpr (NW == 8) {
+        auto tile = [&](int t, auto st_tag) {
+            constexpr int st = decltype(st_tag)::value;
+            const uint32_t s1 = RING1 + st * TB, s2 = RING2 + st * TB;
+            // tile t was issued two iterations ago; the loads of tile t+1 may still be in flight
+            wait_vmcnt<NGRP>();
+            __syncthreads();
+            // every wave has finished tile t-1: its stage is free
+            issue_tile((st + 2) % NST, t + 2);
+
+            // S (owner columns) and dP
+            f32x16 s[2], dp[2];
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    s[blk][r] = 0.f;
+                    dp[blk][r] = 0.f;
+                }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk)
+                    s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(s1, blk, ks), b1[ks], s[blk], 0, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk)
+                    dp[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(s2, blk, ks), b2[ks], dp[blk], 0, 0, 0);
+
+            // does this wave's part of the tile touch the ragged end or the causal diagonal?
+            const int r0 = t * BN;  // first streamed row of the tile
+            bool need_mask = r0 + BN > S_str;
+            if (CAUSAL)
+                need_mask = need_mask || (KEY_OWNER ? (r0 < o0w + 31) : (r0 + BN - 1 > o0w));
+
+            // P = exp(S*scale - LSE), dS = P (dP - Delta), both rounded to bf16 as B operands
+            bf16x8 pb[2][2], dsb[2][2];
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    float lse2[4], dl[4];
+                    if (KEY_OWNER) {
+                        const uint32_t aux = lds0 + AUX + st * (NW * 256) + (32 * blk + 8 * a + 4 * g) * 4;
+                        const f32x4 l4 = *(ATTN_LDS_PTR(const f32x4))(uintptr_t)aux;
+                        const f32x4 d4 = *(ATTN_LDS_PTR(const f32x4))(uintptr_t)(aux + 256);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            lse2[i] = l4[i] * kLog2e;
+                            dl[i] = d4[i];
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            lse2[i] = lse2_own;
+                            dl[i] = delta_own;
+                        }
+                    }
+                    float pv[4], dsv[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int r = 4 * a + i;
+                        float pe = __builtin_amdgcn_exp2f(fmaf(s[blk][r], p.c, -lse2[i]));
+                        if (need_mask) {
+                            const int sr = r0 + 32 * blk + 8 * a + 4 * g + i;  // streamed row of this element
+                            bool ok = sr < S_str;
+                            if (CAUSAL)
+                                ok = ok && (KEY_OWNER ? (sr >= own) : (sr <= own));
+                            pe = ok ? pe : 0.f;
+                        }
+                        pv[i] = pe;
+                        dsv[i] = pe * (dp[blk][r] - dl[i]);
+                    }
+                    const f32x2 p01 = {pv[0], pv[1]}, p23 = {pv[2], pv[3]};
+                    const f32x2 d01 = {dsv[0], dsv[1]}, d23 = {dsv[2], dsv[3]};
+                    const bf16x2 pa = __builtin_convertvector(p01, bf16x2), pc = __builtin_convertvector(p23, bf16x2);
+                    const bf16x2 da = __builtin_convertvector(d01, bf16x2), dc = __builtin_convertvector(d23, bf16x2);
+                    const int e0 = 4 * (a & 1);
+                    pb[blk][a >> 1][e0 + 0] = pa[0], pb[blk][a >> 1][e0 + 1] = pa[1];
+                    pb[blk][a >> 1][e0 + 2] = pc[0], pb[blk][a >> 1][e0 + 3] = pc[1];
+                    dsb[blk][a >> 1][e0 + 0] = da[0], dsb[blk][a >> 1][e0 + 1] = da[1];
+                    dsb[blk][a >> 1][e0 + 2] = dc[0], dsb[blk][a >> 1][e0 + 3] = dc[1];
+                }
+
+            // contractions over the streamed index: dK^T += Q^T dS (or dQ^T += K^T dS^T), dV^T += dO^T P
+#pragma unroll
+            for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    acc1[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(s1, ch, db), dsb[ch >> 1][ch & 1], acc1[db], 0, 0, 0);
+                    if (KEY_OWNER)
+                        acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(s2, ch, db), pb[ch >> 1][ch & 1], acc2[db], 0, 0, 0);
+                }
+        };
+        int t = t_begin;
+        for (; t + 3 <= t_end; t += 3) {
+            tile(t, std::integral_constant<int, 0>{});
+            tile(t + 1, std::integral_constant<int, 1>{});
+            tile(t + 2, std::integral_constant<int, 2>{});
+        }
+        if (t < t_end)
+            tile(t, std::integral_constant<int, 0>{});
+        if (t + 1 < t_end)
+            tile(t + 1, std::integral_constant<int, 1>{});
+    } else {
+        for (int t = t_begin; t < t_end; ++t) {
+            const int st = (t - t_begin) % NST;
         const uint32_t s1 = RING1 + st * TB, s2 = RING2 + st * TB;
         // tile t was issued two iterations ago; the loads of tile t+1 may still be in flight
         wait_vmcnt<NGRP>();
@@ -269,7 +383,7 @@ __global__ __launch_bounds__(256) void attn_bwd_sweep_kernel(const BwdParams p)
             for (int a = 0; a < 4; ++a) {
                 float lse2[4], dl[4];
                 if (KEY_OWNER) {
-                    const uint32_t aux = lds0 + AUX + st * 1024 + (32 * blk + 8 * a + 4 * g) * 4;
+                    const uint32_t aux = lds0 + AUX + st * (NW * 256) + (32 * blk + 8 * a + 4 * g) * 4;
                     const f32x4 l4 = *(ATTN_LDS_PTR(const f32x4))(uintptr_t)aux;
                     const f32x4 d4 = *(ATTN_LDS_PTR(const f32x4))(uintptr_t)(aux + 256);
 #pragma unroll
@@ -319,6 +433,7 @@ __global__ __launch_bounds__(256) void attn_bwd_sweep_kernel(const BwdParams p)
                 if (KEY_OWNER)
                     acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(s2, ch, db), pb[ch >> 1][ch & 1], acc2[db], 0, 0, 0);
             }
+        }
     }
     // no direct load may still be writing LDS when the workgroup retires
     wait_vmcnt<0>();
