@@ -117,6 +117,10 @@ def main():
                     help="element type (default: bf16 for --config, f16 for --paper-seq)")
     ap.add_argument("--bwd", action="store_true",
                     help="time the backward pass (attn_bwd: Delta kernel + two sweeps) instead; bf16 only")
+    ap.add_argument("--splitkv", type=int, default=0,
+                    help="time attn_fwd_splitkv with this many key ranges on the long-context shape "
+                         "(B=1, H=8, S_q=256, S_kv=131072, D=128, non-causal; --long-skv changes S_kv)")
+    ap.add_argument("--long-skv", type=int, default=131072)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB device copy instead (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -142,7 +146,17 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": args.steps}))
         return
     dev = torch.device("cuda:0")
-    if args.paper_seq:
+    if args.splitkv:
+        cfg = dict(name="long_B1_H8_Sq256_Skv%d_D128_full_split%d" % (args.long_skv, args.splitkv), B=1, H=8, S_q=256,
+                   S_kv=args.long_skv, D=128, causal=False, seed=300, sharp=False, dtype="bf16")
+        tdt = torch.bfloat16
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg["seed"])
+        draw = lambda S: torch.randn((1, cfg["H"], S, cfg["D"]), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        qd, kd, vd = draw(cfg["S_q"]), draw(cfg["S_kv"]), draw(cfg["S_kv"])
+        scale = synth.default_scale(cfg["D"])
+        q = k = v = None
+    elif args.paper_seq:
         cfg = synth.paper_workload(args.paper_seq, causal=False)
         cfg["dtype"] = args.dtype or "f16"
         cfg["name"] = cfg["name"].replace("_f16", "_" + cfg["dtype"])
@@ -175,6 +189,11 @@ def main():
             print("bench.py: --bwd runs in bf16 (use --dtype bf16 with --paper-seq)", file=sys.stderr)
             sys.exit(2)
         return bench_bwd(args, cfg, qd, kd, vd, scale, stream, flops)
+    if args.splitkv:
+        ws = torch.empty((binding.attn_fwd_splitkv_workspace_bytes(cfg["B"], cfg["H"], cfg["S_q"], cfg["D"], args.splitkv),),
+                         dtype=torch.uint8, device=dev)
+        entry = lambda q_, k_, v_, o_, lse_, causal, scale, stream: binding.attn_fwd_splitkv(
+            q_, k_, v_, args.splitkv, o_, lse_, ws, causal=causal, scale=scale, stream=stream)
     step = lambda: entry(qd, kd, vd, o, lse, causal=cfg["causal"], scale=scale, stream=stream)
     for _ in range(args.warmup):
         step()

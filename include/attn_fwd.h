@@ -35,7 +35,9 @@ typedef enum attn_status {
     ATTN_ERR_UNSUPPORTED_D = -3, /* D not in {64, 128, 256} */
     ATTN_ERR_ALIGN = -4,         /* q, k, v or o not 16-byte aligned, or lse not 4-byte aligned */
     ATTN_ERR_SCALE = -5,         /* scale is NaN, infinite or negative */
-    ATTN_ERR_LAUNCH = -6         /* the HIP runtime refused the launch (see hipGetLastError) */
+    ATTN_ERR_LAUNCH = -6,        /* the HIP runtime refused the launch (see hipGetLastError) */
+    ATTN_ERR_UNSUPPORTED = -7,   /* the entry point does not implement this combination of arguments */
+    ATTN_ERR_WORKSPACE = -8      /* the workspace is too small */
 } attn_status;
 
 /*
@@ -85,6 +87,35 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
 int attn_fwd_f16(const void *q, const void *k, const void *v, void *o, float *lse,
                  int B, int H, int S_q, int S_kv, int D, int causal, float scale,
                  void *stream);
+
+/*
+ * attn_fwd_splitkv -- attn_fwd with the keys cut into n_split ranges that run as separate
+ * workgroups, for shapes whose B * H * ceil(S_q / 256) query tiles cannot fill the 256 compute
+ * units (long S_kv, few heads or queries).  Each range runs the loop of Fig. 1a on its keys and
+ * leaves a normalised partial output and its log-sum-exp in the workspace; a second kernel merges
+ * them:  lse = ln sum_s exp(lse_s),  o = sum_s exp(lse_s - lse) o_s  -- the accumulator
+ * rescaling of Section 6.2 applied once more, across workgroups.
+ *
+ * Arguments, layout, ownership and error behaviour are those of attn_fwd, plus:
+ *   workspace        device pointer, 16-byte aligned, owned by the caller, overwritten; must stay
+ *                    valid until the work on `stream` has completed
+ *   workspace_bytes  its size; at least attn_fwd_splitkv_workspace_bytes(B, H, S_q, D, n_split),
+ *                    else ATTN_ERR_WORKSPACE
+ *   n_split          1 .. 256 requested key ranges; ranges are rounded up to whole 64-key tiles,
+ *                    so fewer may be used (one range = a plain attn_fwd launch)
+ *   D                64 or 128 (256 returns ATTN_ERR_UNSUPPORTED_D)
+ *   causal           must be 0 (ATTN_ERR_UNSUPPORTED otherwise)
+ *   scale            finite and > 0
+ * Results are bitwise reproducible for a given n_split; they differ from attn_fwd's in the last
+ * bits (another summation order).
+ */
+int attn_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *lse,
+                     void *workspace, long long workspace_bytes, int n_split,
+                     int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+                     void *stream);
+
+/* Bytes of workspace attn_fwd_splitkv needs: n_split * B * H * S_q * (D + 1) * 4; -1 on invalid arguments. */
+long long attn_fwd_splitkv_workspace_bytes(int B, int H, int S_q, int D, int n_split);
 
 /* Static, NUL-terminated description of an attn_status value; never freed. */
 const char *attn_strerror(int status);

@@ -21,6 +21,11 @@ _lib.attn_fwd.restype = ctypes.c_int
 _lib.attn_fwd.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
 _lib.attn_fwd_f16.restype = ctypes.c_int
 _lib.attn_fwd_f16.argtypes = _lib.attn_fwd.argtypes
+_lib.attn_fwd_splitkv.restype = ctypes.c_int
+_lib.attn_fwd_splitkv.argtypes = ([ctypes.c_void_p] * 6 + [ctypes.c_longlong, ctypes.c_int] + [ctypes.c_int] * 6
+                                  + [ctypes.c_float, ctypes.c_void_p])
+_lib.attn_fwd_splitkv_workspace_bytes.restype = ctypes.c_longlong
+_lib.attn_fwd_splitkv_workspace_bytes.argtypes = [ctypes.c_int] * 5
 _lib.attn_bwd.restype = ctypes.c_int
 _lib.attn_bwd.argtypes = [ctypes.c_void_p] * 10 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
 _lib.attn_strerror.restype = ctypes.c_char_p
@@ -35,6 +40,8 @@ ATTN_ERR_UNSUPPORTED_D = -3
 ATTN_ERR_ALIGN = -4
 ATTN_ERR_SCALE = -5
 ATTN_ERR_LAUNCH = -6
+ATTN_ERR_UNSUPPORTED = -7
+ATTN_ERR_WORKSPACE = -8
 
 
 class AttnError(RuntimeError):
@@ -161,3 +168,50 @@ def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, cau
     if rc != ATTN_OK:
         raise AttnError(rc)
     return dq, dk, dv
+
+
+def attn_fwd_splitkv_workspace_bytes(B, H, S_q, D, n_split):
+    return int(_lib.attn_fwd_splitkv_workspace_bytes(B, H, S_q, D, n_split))
+
+
+def attn_fwd_splitkv_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, ws_ptr, ws_bytes, n_split,
+                         B, H, S_q, S_kv, D, causal, scale, stream_ptr):
+    """The C entry point attn_fwd_splitkv with raw integer addresses; returns the attn_status."""
+    return int(_lib.attn_fwd_splitkv(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, ws_ptr, ws_bytes, n_split,
+                                     B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
+
+
+def attn_fwd_splitkv(q, k, v, n_split, o=None, lse=None, workspace=None, causal=False, scale=None, stream=None):
+    """attn_fwd_splitkv on torch device tensors (bf16).  `workspace`: a contiguous GPU tensor of at least
+    attn_fwd_splitkv_workspace_bytes(...) bytes (allocated when not given).  Returns (o, lse)."""
+    import torch
+
+    for t in (q, k, v):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise TypeError("q, k, v must be contiguous 4-D bf16 tensors on the GPU")
+    B, H, S_q, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
+        raise ValueError("q, k, v shapes do not agree")
+    S_kv = k.shape[2]
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty((B, H, S_q), dtype=torch.float32, device=q.device) if lse is None else lse
+    if o.dtype != torch.bfloat16 or o.shape != q.shape or not o.is_contiguous() or not o.is_cuda:
+        raise TypeError("o must be a contiguous bf16 GPU tensor shaped like q")
+    if lse.dtype != torch.float32 or tuple(lse.shape) != (B, H, S_q) or not lse.is_contiguous() or not lse.is_cuda:
+        raise TypeError("lse must be a contiguous fp32 GPU tensor [B,H,S_q]")
+    need = attn_fwd_splitkv_workspace_bytes(B, H, S_q, D, n_split)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=q.device)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous GPU tensor")
+    if scale is None:
+        scale = 1.0 / float(D) ** 0.5
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    with torch.cuda.device(q.device):
+        rc = attn_fwd_splitkv_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), n_split,
+                                  B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
+    if rc != ATTN_OK:
+        raise AttnError(rc)
+    return o, lse

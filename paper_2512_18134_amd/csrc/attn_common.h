@@ -62,6 +62,11 @@ struct Params {
     int total_wg;  // B*H*n_qt
     float c;       // scale * log2(e): the softmax runs in the base-2 domain
     float scale;
+    // split-KV launches only: the keys are cut into n_split ranges of split_len keys (a multiple of
+    // the K/V tile), every range is a workgroup of its own and writes a normalised partial result
+    int n_split, split_len;
+    float *o_part;    // [n_split][B*H*S_q][D] fp32
+    float *lse_part;  // [n_split][B*H*S_q] fp32
 };
 
 // Workgroup id -> (batch*head, query tile).

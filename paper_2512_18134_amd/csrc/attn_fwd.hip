@@ -11,6 +11,7 @@
 #include "attn_fwd_asm2.h"
 #include "attn_fwd_pipe.h"
 #include "attn_fwd_simple.h"
+#include "attn_splitkv.h"
 
 namespace {
 
@@ -144,7 +145,81 @@ static int validate(const void *q, const void *k, const void *v, void *o, float 
     p.total_wg = 0;
     p.c = scale * 1.44269504088896340736f;
     p.scale = scale;
+    p.n_split = 1;
+    p.split_len = 0;
+    p.o_part = nullptr;
+    p.lse_part = nullptr;
     return ATTN_OK;
+}
+
+// key range of one split: a multiple of the 64-key tile; returns the number of non-empty ranges
+static int split_plan(int S_kv, int n_split, int &split_len)
+{
+    const int per = (S_kv + n_split - 1) / n_split;
+    split_len = (per + 63) / 64 * 64;
+    return (S_kv + split_len - 1) / split_len;
+}
+
+extern "C" long long attn_fwd_splitkv_workspace_bytes(int B, int H, int S_q, int D, int n_split)
+{
+    if (B < 1 || H < 1 || S_q < 1 || n_split < 1 || n_split > 256 || (D != 64 && D != 128))
+        return -1;
+    return (long long)n_split * B * H * S_q * (D + 1) * 4;
+}
+
+extern "C" int attn_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *lse, void *workspace,
+                                long long workspace_bytes, int n_split, int B, int H, int S_q, int S_kv, int D,
+                                int causal, float scale, void *stream)
+{
+    Params p;
+    const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    if (D == 256)
+        return ATTN_ERR_UNSUPPORTED_D;
+    if (causal)
+        return ATTN_ERR_UNSUPPORTED;
+    if (!(scale > 0.f))
+        return ATTN_ERR_SCALE;
+    if (n_split < 1 || n_split > 256 || (long long)S_kv * D * 2 >= (1LL << 31))
+        return ATTN_ERR_SHAPE;
+    if (!workspace)
+        return ATTN_ERR_NULL;
+    if ((uintptr_t)workspace & 15)
+        return ATTN_ERR_ALIGN;
+    if (workspace_bytes < attn_fwd_splitkv_workspace_bytes(B, H, S_q, D, n_split))
+        return ATTN_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n_eff = split_plan(S_kv, n_split, p.split_len);
+    if (n_eff == 1)  // one range: the plain kernel writes o and lse itself
+        return D == 64 ? launch_asm<64>(p, B * H, 0, st) : launch_asm<128>(p, B * H, 0, st);
+    const long long n_rows = (long long)B * H * S_q;
+    p.n_split = n_eff;
+    p.o_part = static_cast<float *>(workspace);
+    p.lse_part = p.o_part + (long long)n_eff * n_rows * D;
+    constexpr int BM = 256;
+    p.n_qt = (S_q + BM - 1) / BM;
+    const long long total = (long long)B * H * p.n_qt * n_eff;
+    if (total > 0x7fffffffLL)
+        return ATTN_ERR_SHAPE;
+    p.total_wg = (int)total;
+    const int lds = 8 * 64 * D * 2;
+    auto kern = D == 64 ? attn::attn_fwd_asm_kernel<64, false, false, true> : attn::attn_fwd_asm_kernel<128, false, false, true>;
+    if (!allow_lds(kern, lds))
+        return ATTN_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(512), lds, st, p);
+    if (hipGetLastError() != hipSuccess)
+        return ATTN_ERR_LAUNCH;
+    const int rpb = 256 / (D / 4);
+    const long long blocks = (n_rows + rpb - 1) / rpb;
+    const unsigned grid = (unsigned)(blocks < 8192 ? blocks : 8192);
+    if (D == 64)
+        hipLaunchKernelGGL(attn::attn_splitkv_merge_kernel<64>, dim3(grid), dim3(256), 0, st, p.o_part, p.lse_part,
+                           static_cast<attn::bf16_t *>(o), lse, n_rows, n_eff);
+    else
+        hipLaunchKernelGGL(attn::attn_splitkv_merge_kernel<128>, dim3(grid), dim3(256), 0, st, p.o_part, p.lse_part,
+                           static_cast<attn::bf16_t *>(o), lse, n_rows, n_eff);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
 extern "C" int attn_fwd_f16(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
@@ -219,8 +294,12 @@ extern "C" const char *attn_strerror(int status)
         return "scale must be finite and >= 0";
     case ATTN_ERR_LAUNCH:
         return "the HIP runtime rejected the kernel launch";
+    case ATTN_ERR_UNSUPPORTED:
+        return "this entry point does not implement the requested combination (e.g. causal split-KV)";
+    case ATTN_ERR_WORKSPACE:
+        return "the workspace is smaller than attn_fwd_splitkv_workspace_bytes() asks for";
     }
     return "unknown attn_status";
 }
 
-extern "C" int attn_version(void) { return 300; }
+extern "C" int attn_version(void) { return 400; }

@@ -36,7 +36,7 @@ def test_header_symbols_are_exported(binding):
 
 def test_version_and_strerror(binding):
     assert binding.attn_version() >= 100
-    for code in range(0, -7, -1):
+    for code in range(0, -9, -1):
         msg = binding.attn_strerror(code)
         assert isinstance(msg, str) and msg and "unknown" not in msg
     assert "unknown" in binding.attn_strerror(-99)
@@ -79,6 +79,34 @@ def test_f16_entry_validates_like_the_bf16_one_and_narrows_d_and_scale(binding):
     for s in (float("nan"), float("inf"), -1.0, 0.0):
         assert f(scale=s) == b.ATTN_ERR_SCALE
     assert f(S_kv=1 << 24, D=128) == b.ATTN_ERR_SHAPE  # one head of K beyond 32-bit byte offsets
+
+
+def test_splitkv_entry_validates_before_any_launch(binding):
+    b = binding
+    ok = 0x1000
+    names = ("q", "k", "v", "o", "lse", "ws")
+    def f(**kw):
+        ptrs = [kw.get(n, ok) for n in names]
+        ws_bytes = kw.get("ws_bytes", 1 << 40)
+        rest = [kw.get(n, d) for n, d in (("n_split", 4), ("B", 1), ("H", 1), ("S_q", 8), ("S_kv", 8), ("D", 64),
+                                           ("causal", 0), ("scale", 0.125), ("stream", 0))]
+        return b.attn_fwd_splitkv_raw(*(ptrs + [ws_bytes] + rest))
+    for n in names:
+        assert f(**{n: 0}) == b.ATTN_ERR_NULL
+    for n in ("B", "H", "S_q", "S_kv"):
+        assert f(**{n: 0}) == b.ATTN_ERR_SHAPE
+    for ns in (0, -1, 257):
+        assert f(n_split=ns) == b.ATTN_ERR_SHAPE
+    for D in (0, 32, 256):
+        assert f(D=D) == b.ATTN_ERR_UNSUPPORTED_D
+    assert f(causal=1) == b.ATTN_ERR_UNSUPPORTED
+    assert f(scale=0.0) == b.ATTN_ERR_SCALE
+    assert f(ws=ok + 8) == b.ATTN_ERR_ALIGN
+    need = b.attn_fwd_splitkv_workspace_bytes(1, 1, 8, 64, 4)
+    assert need == 4 * 8 * 65 * 4
+    assert f(ws_bytes=need - 1) == b.ATTN_ERR_WORKSPACE
+    assert b.attn_fwd_splitkv_workspace_bytes(1, 1, 8, 256, 4) == -1
+    assert b.attn_fwd_splitkv_workspace_bytes(1, 1, 8, 64, 0) == -1
 
 
 def test_bwd_entry_validates_before_any_launch(binding):
