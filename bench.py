@@ -73,7 +73,7 @@ def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops):
     d_o = torch.randn(qd.shape, generator=gen, device=qd.device, dtype=torch.float32).to(qd.dtype)
     o, lse = binding.attn_fwd(qd, kd, vd, causal=cfg["causal"], scale=scale, stream=stream)
     dq, dk, dv = torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd)
-    ws = torch.empty(qd.shape[:3], dtype=torch.float32, device=qd.device)
+    ws = torch.empty((2,) + tuple(qd.shape[:3]), dtype=torch.float32, device=qd.device)
     step = lambda: binding.attn_bwd(qd, kd, vd, o, d_o, lse, dq, dk, dv, ws, causal=cfg["causal"], scale=scale,
                                     stream=stream)
     for _ in range(args.warmup):

@@ -34,9 +34,10 @@ extern "C" {
  *   dq         device pointer, bf16, [B][H][S_q][D]; every element is overwritten
  *   dk, dv     device pointers, bf16, [B][H][S_kv][D]; every element is overwritten
  *              (keys that no query sees get zeros)
- *   delta_ws   device pointer, fp32, [B][H][S_q]: workspace owned by the caller; the call
- *              overwrites it (it holds Delta) and reads it back on the same stream
- *   B, H, S_q, S_kv   >= 1; S_q * D and S_kv * D below 2^30
+ *   delta_ws   device pointer, fp32, 2 * B * H * S_q elements: workspace owned by the caller; the
+ *              call overwrites it (first half: lse * log2(e), second half: Delta) and reads it
+ *              back on the same stream
+ *   B, H, S_q, S_kv   >= 1; S_q * D and S_kv * D below 2^30, B * H * S_q below 2^28
  *   D          64 or 128 (256 returns ATTN_ERR_UNSUPPORTED_D)
  *   causal, scale, stream   as in attn_fwd; they must be the values the forward call used
  *

@@ -129,7 +129,7 @@ def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, cau
     """attn_bwd on torch device tensors (include/attn_bwd.h).
 
     q, o, d_o [B,H,S_q,D], k, v [B,H,S_kv,D]: contiguous bf16 on the GPU; lse fp32 [B,H,S_q] as
-    written by attn_fwd.  dq, dk, dv (bf16) and the fp32 workspace delta_ws [B,H,S_q] are
+    written by attn_fwd.  dq, dk, dv (bf16) and the fp32 workspace delta_ws (2*B*H*S_q floats) are
     allocated when not given.  Asynchronous on `stream`.  Returns (dq, dk, dv).
     """
     import torch
@@ -150,13 +150,13 @@ def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, cau
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv
     if delta_ws is None:
-        delta_ws = torch.empty((B, H, S_q), dtype=torch.float32, device=q.device)
+        delta_ws = torch.empty((2, B, H, S_q), dtype=torch.float32, device=q.device)
     for t, like in ((dq, q), (dk, k), (dv, v)):
         if t.dtype != dt or t.shape != like.shape or not t.is_contiguous() or not t.is_cuda:
             raise TypeError("dq, dk, dv must be contiguous bf16 GPU tensors shaped like q, k, v")
-    if (delta_ws.dtype != torch.float32 or delta_ws.numel() < B * H * S_q or not delta_ws.is_contiguous()
+    if (delta_ws.dtype != torch.float32 or delta_ws.numel() < 2 * B * H * S_q or not delta_ws.is_contiguous()
             or not delta_ws.is_cuda):
-        raise TypeError("delta_ws must be a contiguous fp32 GPU tensor with at least B*H*S_q elements")
+        raise TypeError("delta_ws must be a contiguous fp32 GPU tensor with at least 2*B*H*S_q elements")
     if scale is None:
         scale = 1.0 / float(D) ** 0.5
     if stream is None:

@@ -37,6 +37,13 @@ def generate_sources(verbose=False):
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
+    gen3 = os.path.join(HERE, "csrc", "gen_attn_bwd_loop.py")
+    for kind, d in (("kv", 128), ("q", 128)):
+        out = os.path.join(out_dir, "attn_bwd_loop_%s_d%d.inc" % (kind, d))
+        cmd = [sys.executable, gen3, kind, str(d), out]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
 
 
 def build_library(verbose=False):

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 
 #include "attn_bwd.h"  // the C declaration (include/)
+#include "attn_bwd_asm.h"
 #include "attn_bwd_kernels.h"
 #include "attn_fwd.h"  // attn_status
 
@@ -42,8 +43,26 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
         if (hipGetLastError() != hipSuccess)
             return ATTN_ERR_LAUNCH;
     }
-    int rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream)
+    int rc;
+    if constexpr (D == 128) {
+        // hand-scheduled key-owner sweep (needs scale > 0); ATTN_BWD_KERNEL=plain (debug only) keeps the
+        // compiler-scheduled one
+        static const bool plain = [] {
+            const char *e = getenv("ATTN_BWD_KERNEL");
+            return e && e[0] == 'p';
+        }();
+        if (!plain && p.scale > 0.f) {
+            constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
+            rc = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true>, p, BH, p.S_kv, 4, LDSA, stream)
+                        : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true>, p, BH, p.S_kv, 4, LDSA, stream);
+        } else {
+            rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream)
+                        : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream);
+        }
+    } else {
+        rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream)
                     : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream);
+    }
     if (rc != ATTN_OK)
         return rc;
     return causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream)
@@ -66,7 +85,7 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     if (BH > 0x7fffffffLL || BH * (long long)(S_q > S_kv ? S_q : S_kv) > (1LL << 40) / D)
         return ATTN_ERR_SHAPE;
     // one head of any tensor is addressed with 32-bit byte offsets
-    if ((long long)(S_q > S_kv ? S_q : S_kv) * D * 2 >= (1LL << 31))
+    if ((long long)(S_q > S_kv ? S_q : S_kv) * D * 2 >= (1LL << 31) || BH * S_q * 8 >= (1LL << 31))
         return ATTN_ERR_SHAPE;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)d_o | (uintptr_t)dq | (uintptr_t)dk |
          (uintptr_t)dv) & 15)
@@ -82,7 +101,8 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     p.o = static_cast<const attn::bf16_t *>(o);
     p.d_o = static_cast<const attn::bf16_t *>(d_o);
     p.lse = lse;
-    p.delta = delta_ws;
+    p.lse2 = delta_ws;
+    p.delta = delta_ws + BH * S_q;
     p.dq = static_cast<attn::bf16_t *>(dq);
     p.dk = static_cast<attn::bf16_t *>(dk);
     p.dv = static_cast<attn::bf16_t *>(dv);

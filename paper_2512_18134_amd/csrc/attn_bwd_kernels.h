@@ -33,7 +33,8 @@ namespace attn {
 struct BwdParams {
     const bf16_t *q, *k, *v, *o, *d_o;
     const float *lse;
-    float *delta;  // [B][H][S_q] workspace: written by the delta kernel, read by the sweeps
+    float *lse2;   // workspace, [B][H][S_q]: LSE * log2(e), written by the delta kernel, read by the sweeps
+    float *delta;  // workspace, [B][H][S_q], directly behind lse2: Delta
     bf16_t *dq, *dk, *dv;
     int S_q, S_kv;
     int n_t;       // owner tiles per (b,h) of the launched sweep
@@ -52,7 +53,7 @@ __device__ __forceinline__ void dma4(uint32_t lds_addr, const void *base, uint32
                  : "memory");
 }
 
-// Delta[r] = sum_d dO[r][d] * O[r][d] (fp32).  D/8 lanes per row, 16 bytes per lane.
+// Delta[r] = sum_d dO[r][d] * O[r][d] (fp32) and LSE'[r] = LSE[r] * log2(e).  D/8 lanes per row, 16 bytes per lane.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p)
 {
@@ -70,8 +71,10 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p)
 #pragma unroll
         for (int m = LPR / 2; m >= 1; m >>= 1)
             acc += __shfl_xor(acc, m, 64);
-        if (sub == 0)
+        if (sub == 0) {
             p.delta[r] = acc;
+            p.lse2[r] = p.lse[r] * 1.44269504088896340736f;
+        }
     }
 }
 
