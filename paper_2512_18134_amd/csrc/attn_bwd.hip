@@ -65,6 +65,18 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
     }
     if (rc != ATTN_OK)
         return rc;
+    if constexpr (D == 128) {
+        // hand-scheduled query-owner sweep; ATTN_BWD_KERNEL=plain (debug only) keeps the compiler-scheduled one
+        static const bool plain_q = [] {
+            const char *e = getenv("ATTN_BWD_KERNEL");
+            return e && e[0] == 'p';
+        }();
+        if (!plain_q && p.scale > 0.f) {
+            constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
+            return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false>, p, BH, p.S_q, 4, LDSA, stream)
+                          : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false>, p, BH, p.S_q, 4, LDSA, stream);
+        }
+    }
     return causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream)
                   : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream);
 }
