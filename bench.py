@@ -62,7 +62,24 @@ def cpu_baseline(cfg, q, k, v, scale, target_seconds=15.0):
             "sample": "%d of %d rows (uniform random, seed 1234), %.1f s wall, fp64 two-pass oracle, OpenMP" % (n, total_rows, dt)}
 
 
-def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops):
+def cpu_baseline_bwd(cfg, q, k, v, d_o, scale, target_seconds=15.0):
+    """Time the fp64 backward oracle on whole heads of the same workload (bounded)."""
+    from oracle import attn_oracle
+    BH = cfg["B"] * cfg["H"]
+    per_head = 2.5 * 4.0 * cfg["D"] * (cfg["S_q"] * (cfg["S_q"] + 1) // 2 if cfg["causal"] and cfg["S_q"] == cfg["S_kv"]
+                                       else cfg["S_q"] * cfg["S_kv"])
+    t0 = time.perf_counter()
+    attn_oracle.attn_bwd_ref(q, k, v, d_o, cfg["causal"], scale, heads=np.array([0], dtype=np.int64))
+    dt1 = time.perf_counter() - t0
+    n = int(max(1, min(BH - 1, target_seconds / max(dt1, 1e-6))))
+    t0 = time.perf_counter()
+    attn_oracle.attn_bwd_ref(q, k, v, d_o, cfg["causal"], scale, heads=np.arange(1, 1 + n, dtype=np.int64) % BH)
+    dt = time.perf_counter() - t0
+    return {"value": n * per_head / dt / 1e12, "unit": "TFLOP/s", "cores": attn_oracle.max_threads(), "kind": "oracle",
+            "sample": "%d of %d heads in full, %.1f s wall, fp64 backward oracle, OpenMP" % (n, BH, dt)}
+
+
+def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops, host_qkv):
     """One step = one attn_bwd call (Delta kernel, key-owner sweep, query-owner sweep).  Algorithmic work:
     the five products of the backward pass = 2.5x the forward FLOP (the library computes seven)."""
     import torch
@@ -92,7 +109,7 @@ def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops):
     ms_per_step = wall * 1e3 / args.steps
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (float(np.mean(kern_ms)) * 1e-3) / 1e12
-    print(json.dumps({
+    out = {
         "metric": "attention bwd TFLOP/s at 1 GPU (bf16, D=%d, S=%d, %s)" % (cfg["D"], cfg["S_q"], "causal" if cfg["causal"] else "non-causal"),
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -102,7 +119,12 @@ def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops):
                    "kernel_ms_avg": float(np.mean(kern_ms)), "kernel_ms_min": float(np.min(kern_ms))},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
-    }), flush=True)
+    }
+    if not args.no_cpu_baseline:
+        to_bits = lambda t: t.cpu().view(torch.int16).numpy().view(np.uint16)
+        q, k, v = host_qkv if host_qkv[0] is not None else (to_bits(qd), to_bits(kd), to_bits(vd))
+        out["cpu_baseline"] = cpu_baseline_bwd(cfg, q, k, v, to_bits(d_o), scale)
+    print(json.dumps(out), flush=True)
 
 
 def main():
@@ -188,7 +210,7 @@ def main():
         if cfg["dtype"] != "bf16":
             print("bench.py: --bwd runs in bf16 (use --dtype bf16 with --paper-seq)", file=sys.stderr)
             sys.exit(2)
-        return bench_bwd(args, cfg, qd, kd, vd, scale, stream, flops)
+        return bench_bwd(args, cfg, qd, kd, vd, scale, stream, flops, (q, k, v))
     if args.splitkv:
         ws = torch.empty((binding.attn_fwd_splitkv_workspace_bytes(cfg["B"], cfg["H"], cfg["S_q"], cfg["D"], args.splitkv),),
                          dtype=torch.uint8, device=dev)

@@ -30,6 +30,7 @@ Hazards handled by construction (the assembler inserts no wait states):
 
 usage: gen_attn_bwd_loop.py <kv|q> <D> <out.inc>
 """
+import os
 import sys
 
 
@@ -48,8 +49,9 @@ class Gen:
         self.NLD = self.TB // (self.NW * 1024)
         assert self.NLD >= 1
         self.NSET = 2 if key_owner else 1            # accumulator sets: (dK, dV) or (dQ)
-        self.NF, self.PFD = NF, PFD
         self.NC = self.NSET * self.DB                # contraction MFMAs per 16-row chunk
+        PFD = min(PFD, self.NC)                      # the prefetched operands belong to the first chunk (see drain)
+        self.NF, self.PFD = NF, PFD
         self.NM = 2 * self.NC + 2 * self.KS          # MFMA slots per iteration
         self.NGRP = 2 * self.NLD + (1 if key_owner else 0)  # direct loads per wave and tile
         assert self.NM % NF == 0 and PFD < NF
@@ -105,6 +107,8 @@ class Gen:
         self.s_ptr1, self.s_ptr2 = 50, 52
         self.s_t2, self.s_t3 = 54, 55
         self.lines = []
+        # timing experiments only (results are wrong with any of these set): drop parts of the loop
+        self.exp = set(filter(None, os.environ.get("ATTN_GEN_BWD_EXP", "").split(",")))
 
     # ------------------------------------------------------------------ helpers
     def e(self, s):
@@ -265,14 +269,16 @@ class Gen:
         n = len(grps)
         def issue(idx, grp, r, t):
             for ins in self.frag_loads(grp, idx % NF, r, t):
-                self.e(ins)
+                if "nolds" not in self.exp:
+                    self.e(ins)
                 self.outstanding.append(idx)
         for i in range(prefetched, min(PFD, n)):
             issue(i, grps[i], rst, tst)
         for i, grp in enumerate(grps):
             last = max(p for p, x in enumerate(self.outstanding) if x == i)
             after = len(self.outstanding) - 1 - last
-            self.e("s_waitcnt lgkmcnt(%d)" % after)
+            if "nolds" not in self.exp:
+                self.e("s_waitcnt lgkmcnt(%d)" % after)
             self.outstanding = self.outstanding[last + 1:]
             self.e(self.mfma_text(grp, i % NF, bf))
             # the fragment buffer of group i+PFD was last read by group i+PFD-NF <= i-1
@@ -285,7 +291,8 @@ class Gen:
             for ins in extra_by_slot.get(i, []):
                 self.e(ins)
             for ins in lds_by_slot.get(i, []):      # other LDS reads: counted, never waited for by index
-                self.e(ins)
+                if "nolds" not in self.exp:
+                    self.e(ins)
                 self.outstanding.append(-1)
             for ins in valu_by_slot.get(i, []):
                 self.e(ins)
@@ -313,8 +320,9 @@ class Gen:
         self.e("s_cbranch_scc1 %s" % L("MASKHI%d_" % b))
         self.e("%s:" % L("MASKHIRET%d_" % b))
         # the loads of the two previous iterations may stay in flight; tile j+1 has landed
-        self.e("s_waitcnt vmcnt(%d)" % (2 * self.NGRP))
-        self.e("s_barrier")
+        if "nobar" not in self.exp:
+            self.e("s_waitcnt vmcnt(%d)" % (2 * self.NGRP))
+            self.e("s_barrier")
         p1, p2 = self.phase1_ops(bf), self.phase2_ops(bf)
         quota = -(-(len(p1) + len(p2)) // NM)
         n1 = -(-len(p1) // quota)
@@ -340,6 +348,10 @@ class Gen:
             "s_addc_u32 s%d, s%d, 0" % (self.s_ptr2 + 1, self.s_ptr2 + 1),
             "s_add_i32 s%d, s%d, 1" % (self.s_tk, self.s_tk),
             "s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j)]
+        if "novalu" in self.exp:
+            valu = {}
+        if "nodma" in self.exp:
+            extra = {2: extra[2]}
         self.stream(self.groups(), bf, rst, tst, valu, extra, lds, self.PFD, nxt)
         if b == NST - 1:
             self.e("s_branch %s" % L("BODY0_"))
@@ -471,6 +483,9 @@ class Gen:
 
 
 if __name__ == "__main__":
-    text = Gen(sys.argv[1] == "kv", int(sys.argv[2])).emit_inc()
+    # ATTN_GEN_BWD_NF / ATTN_GEN_BWD_PFD (timing experiments): fragment buffers and prefetch distance
+    nf = int(os.environ.get("ATTN_GEN_BWD_NF", "4"))
+    pfd = int(os.environ.get("ATTN_GEN_BWD_PFD", "3"))
+    text = Gen(sys.argv[1] == "kv", int(sys.argv[2]), NF=nf, PFD=pfd).emit_inc()
     with open(sys.argv[3], "w") as f:
         f.write(text)
