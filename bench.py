@@ -69,11 +69,13 @@ def cpu_baseline_bwd(cfg, q, k, v, d_o, scale, target_seconds=15.0):
     per_head = 2.5 * 4.0 * cfg["D"] * (cfg["S_q"] * (cfg["S_q"] + 1) // 2 if cfg["causal"] and cfg["S_q"] == cfg["S_kv"]
                                        else cfg["S_q"] * cfg["S_kv"])
     t0 = time.perf_counter()
-    attn_oracle.attn_bwd_ref(q, k, v, d_o, cfg["causal"], scale, heads=np.array([0], dtype=np.int64))
+    dt_name = cfg.get("dtype", "bf16")
+    attn_oracle.attn_bwd_ref(q, k, v, d_o, cfg["causal"], scale, heads=np.array([0], dtype=np.int64), dtype=dt_name)
     dt1 = time.perf_counter() - t0
     n = int(max(1, min(BH - 1, target_seconds / max(dt1, 1e-6))))
     t0 = time.perf_counter()
-    attn_oracle.attn_bwd_ref(q, k, v, d_o, cfg["causal"], scale, heads=np.arange(1, 1 + n, dtype=np.int64) % BH)
+    attn_oracle.attn_bwd_ref(q, k, v, d_o, cfg["causal"], scale, heads=np.arange(1, 1 + n, dtype=np.int64) % BH,
+                             dtype=dt_name)
     dt = time.perf_counter() - t0
     return {"value": n * per_head / dt / 1e12, "unit": "TFLOP/s", "cores": attn_oracle.max_threads(), "kind": "oracle",
             "sample": "%d of %d heads in full, %.1f s wall, fp64 backward oracle, OpenMP" % (n, BH, dt)}
@@ -88,11 +90,12 @@ def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops, host_qkv):
     gen = torch.Generator(device=qd.device)
     gen.manual_seed(cfg["seed"] + 1000)
     d_o = torch.randn(qd.shape, generator=gen, device=qd.device, dtype=torch.float32).to(qd.dtype)
-    o, lse = binding.attn_fwd(qd, kd, vd, causal=cfg["causal"], scale=scale, stream=stream)
+    f16 = cfg["dtype"] == "f16"
+    fwd, bwd = (binding.attn_fwd_f16, binding.attn_bwd_f16) if f16 else (binding.attn_fwd, binding.attn_bwd)
+    o, lse = fwd(qd, kd, vd, causal=cfg["causal"], scale=scale, stream=stream)
     dq, dk, dv = torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd)
     ws = torch.empty((2,) + tuple(qd.shape[:3]), dtype=torch.float32, device=qd.device)
-    step = lambda: binding.attn_bwd(qd, kd, vd, o, d_o, lse, dq, dk, dv, ws, causal=cfg["causal"], scale=scale,
-                                    stream=stream)
+    step = lambda: bwd(qd, kd, vd, o, d_o, lse, dq, dk, dv, ws, causal=cfg["causal"], scale=scale, stream=stream)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -110,10 +113,10 @@ def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops, host_qkv):
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (float(np.mean(kern_ms)) * 1e-3) / 1e12
     out = {
-        "metric": "attention bwd TFLOP/s at 1 GPU (bf16, D=%d, S=%d, %s)" % (cfg["D"], cfg["S_q"], "causal" if cfg["causal"] else "non-causal"),
+        "metric": "attention bwd TFLOP/s at 1 GPU (%s, D=%d, S=%d, %s)" % (cfg["dtype"], cfg["D"], cfg["S_q"], "causal" if cfg["causal"] else "non-causal"),
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": cfg["name"] + "_bwd", "B": cfg["B"], "H": cfg["H"], "S_q": cfg["S_q"], "S_kv": cfg["S_kv"],
                    "D": cfg["D"], "causal": cfg["causal"], "flop_per_step": flops,
                    "kernel_ms_avg": float(np.mean(kern_ms)), "kernel_ms_min": float(np.min(kern_ms))},
@@ -138,7 +141,7 @@ def main():
     ap.add_argument("--dtype", choices=["bf16", "f16"], default=None,
                     help="element type (default: bf16 for --config, f16 for --paper-seq)")
     ap.add_argument("--bwd", action="store_true",
-                    help="time the backward pass (attn_bwd: Delta kernel + two sweeps) instead; bf16 only")
+                    help="time the backward pass (attn_bwd / attn_bwd_f16: Delta kernel + two sweeps) instead")
     ap.add_argument("--splitkv", type=int, default=0,
                     help="time attn_fwd_splitkv with this many key ranges on the long-context shape "
                          "(B=1, H=8, S_q=256, S_kv=131072, D=128, non-causal; --long-skv changes S_kv)")
@@ -207,8 +210,8 @@ def main():
 
     stream = torch.cuda.current_stream(dev)
     if args.bwd:
-        if cfg["dtype"] != "bf16":
-            print("bench.py: --bwd runs in bf16 (use --dtype bf16 with --paper-seq)", file=sys.stderr)
+        if cfg["dtype"] == "f16" and cfg["D"] != 128:
+            print("bench.py: --bwd in fp16 needs D = 128", file=sys.stderr)
             sys.exit(2)
         return bench_bwd(args, cfg, qd, kd, vd, scale, stream, flops, (q, k, v))
     if args.splitkv:

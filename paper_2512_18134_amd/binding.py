@@ -28,6 +28,8 @@ _lib.attn_fwd_splitkv_workspace_bytes.restype = ctypes.c_longlong
 _lib.attn_fwd_splitkv_workspace_bytes.argtypes = [ctypes.c_int] * 5
 _lib.attn_bwd.restype = ctypes.c_int
 _lib.attn_bwd.argtypes = [ctypes.c_void_p] * 10 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
+_lib.attn_bwd_f16.restype = ctypes.c_int
+_lib.attn_bwd_f16.argtypes = _lib.attn_bwd.argtypes
 _lib.attn_strerror.restype = ctypes.c_char_p
 _lib.attn_strerror.argtypes = [ctypes.c_int]
 _lib.attn_version.restype = ctypes.c_int
@@ -125,6 +127,21 @@ def attn_bwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr, dv
                              B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
 
 
+def attn_bwd_f16_raw(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr, dv_ptr, ws_ptr,
+                     B, H, S_q, S_kv, D, causal, scale, stream_ptr):
+    """The C entry point attn_bwd_f16 with raw integer addresses; returns the attn_status."""
+    return int(_lib.attn_bwd_f16(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr, dv_ptr, ws_ptr,
+                                 B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
+
+
+def attn_bwd_f16(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, causal=False, scale=None,
+                 stream=None):
+    """attn_bwd_f16 on torch device tensors: as attn_bwd, with fp16 tensors (D = 128)."""
+    import torch
+    return _marshal_bwd(attn_bwd_f16_raw, torch.float16, q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, causal, scale,
+                        stream)
+
+
 def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, causal=False, scale=None, stream=None):
     """attn_bwd on torch device tensors (include/attn_bwd.h).
 
@@ -133,11 +150,15 @@ def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, cau
     allocated when not given.  Asynchronous on `stream`.  Returns (dq, dk, dv).
     """
     import torch
+    return _marshal_bwd(attn_bwd_raw, torch.bfloat16, q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, causal, scale, stream)
 
-    dt = torch.bfloat16
+
+def _marshal_bwd(entry, dt, q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, causal, scale, stream):
+    import torch
+
     for t in (q, k, v, o, d_o):
         if t.dtype != dt or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
-            raise TypeError("q, k, v, o, d_o must be contiguous 4-D bf16 tensors on the GPU")
+            raise TypeError("q, k, v, o, d_o must be contiguous 4-D %s tensors on the GPU" % dt)
     B, H, S_q, D = q.shape
     if k.shape != v.shape or k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
         raise ValueError("q, k, v shapes do not agree")
@@ -153,7 +174,7 @@ def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, cau
         delta_ws = torch.empty((2, B, H, S_q), dtype=torch.float32, device=q.device)
     for t, like in ((dq, q), (dk, k), (dv, v)):
         if t.dtype != dt or t.shape != like.shape or not t.is_contiguous() or not t.is_cuda:
-            raise TypeError("dq, dk, dv must be contiguous bf16 GPU tensors shaped like q, k, v")
+            raise TypeError("dq, dk, dv must be contiguous GPU tensors shaped and typed like q, k, v")
     if (delta_ws.dtype != torch.float32 or delta_ws.numel() < 2 * B * H * S_q or not delta_ws.is_contiguous()
             or not delta_ws.is_cuda):
         raise TypeError("delta_ws must be a contiguous fp32 GPU tensor with at least 2*B*H*S_q elements")
@@ -162,9 +183,9 @@ def attn_bwd(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, cau
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
     with torch.cuda.device(q.device):
-        rc = attn_bwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
-                          dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), delta_ws.data_ptr(),
-                          B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
+        rc = entry(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
+                   dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), delta_ws.data_ptr(),
+                   B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
     if rc != ATTN_OK:
         raise AttnError(rc)
     return dq, dk, dv

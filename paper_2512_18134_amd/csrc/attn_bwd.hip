@@ -83,9 +83,10 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
 
 }  // namespace
 
-extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
+// host-side validation shared by the entry points; fills `p` on success
+static int validate_bwd(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
                         void *dq, void *dk, void *dv, float *delta_ws, int B, int H, int S_q, int S_kv, int D,
-                        int causal, float scale, void *stream)
+                        float scale, BwdParams &p)
 {
     if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !delta_ws)
         return ATTN_ERR_NULL;
@@ -96,7 +97,7 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     const long long BH = (long long)B * H;
     if (BH > 0x7fffffffLL || BH * (long long)(S_q > S_kv ? S_q : S_kv) > (1LL << 40) / D)
         return ATTN_ERR_SHAPE;
-    // one head of any tensor is addressed with 32-bit byte offsets
+    // one head of any tensor, and the workspace, are addressed with 32-bit byte offsets
     if ((long long)(S_q > S_kv ? S_q : S_kv) * D * 2 >= (1LL << 31) || BH * S_q * 8 >= (1LL << 31))
         return ATTN_ERR_SHAPE;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)d_o | (uintptr_t)dq | (uintptr_t)dk |
@@ -106,7 +107,6 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
         return ATTN_ERR_ALIGN;
     if (!(scale >= 0.f) || isinf(scale))
         return ATTN_ERR_SCALE;
-    BwdParams p;
     p.q = static_cast<const attn::bf16_t *>(q);
     p.k = static_cast<const attn::bf16_t *>(k);
     p.v = static_cast<const attn::bf16_t *>(v);
@@ -125,8 +125,20 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     p.n_rows = BH * S_q;
     p.c = scale * 1.44269504088896340736f;
     p.scale = scale;
+    return ATTN_OK;
+}
+
+extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
+                        void *dq, void *dk, void *dv, float *delta_ws, int B, int H, int S_q, int S_kv, int D,
+                        int causal, float scale, void *stream)
+{
+    BwdParams p;
+    const int rc = validate_bwd(q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    const long long BH = (long long)B * H;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // Debug only: ATTN_BWD_QNW=4 runs the query-owner sweep with one wave per SIMD.
+    // Debug only: ATTN_BWD_QNW=4 runs the compiler-scheduled query-owner sweep with one wave per SIMD.
     static const int qnw = [] {
         const char *e = getenv("ATTN_BWD_QNW");
         return e ? atoi(e) : 8;
@@ -134,4 +146,35 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     if (qnw == 4)
         return D == 64 ? launch_bwd<64, 4>(p, (int)BH, causal, st) : launch_bwd<128, 4>(p, (int)BH, causal, st);
     return D == 64 ? launch_bwd<64, 8>(p, (int)BH, causal, st) : launch_bwd<128, 8>(p, (int)BH, causal, st);
+}
+
+extern "C" int attn_bwd_f16(const void *q, const void *k, const void *v, const void *o, const void *d_o,
+                            const float *lse, void *dq, void *dk, void *dv, float *delta_ws, int B, int H, int S_q,
+                            int S_kv, int D, int causal, float scale, void *stream)
+{
+    BwdParams p;
+    const int rc = validate_bwd(q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    // fp16 runs on the hand-scheduled sweeps only
+    if (D != 128)
+        return ATTN_ERR_UNSUPPORTED_D;
+    if (!(scale > 0.f))
+        return ATTN_ERR_SCALE;
+    const int BH = B * H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        const long long blocks = (p.n_rows + 15) / 16;
+        const unsigned grid = (unsigned)(blocks < 4096 ? blocks : 4096);
+        hipLaunchKernelGGL((attn::attn_bwd_delta_kernel<128, _Float16>), dim3(grid), dim3(256), 0, st, p);
+        if (hipGetLastError() != hipSuccess)
+            return ATTN_ERR_LAUNCH;
+    }
+    constexpr int LDSA = 2 * 6 * 32 * 128 * 2 + 6 * 256;
+    const int rk = causal ? launch_sweep(attn::attn_bwd_asm_kernel<128, true, true, true>, p, BH, S_kv, 4, LDSA, st)
+                          : launch_sweep(attn::attn_bwd_asm_kernel<128, false, true, true>, p, BH, S_kv, 4, LDSA, st);
+    if (rk != ATTN_OK)
+        return rk;
+    return causal ? launch_sweep(attn::attn_bwd_asm_kernel<128, true, false, true>, p, BH, S_q, 4, LDSA, st)
+                  : launch_sweep(attn::attn_bwd_asm_kernel<128, false, false, true>, p, BH, S_q, 4, LDSA, st);
 }

@@ -54,16 +54,17 @@ __device__ __forceinline__ void dma4(uint32_t lds_addr, const void *base, uint32
 }
 
 // Delta[r] = sum_d dO[r][d] * O[r][d] (fp32) and LSE'[r] = LSE[r] * log2(e).  D/8 lanes per row, 16 bytes per lane.
-template <int D>
+template <int D, typename ELEM = bf16_t>
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p)
 {
+    typedef ELEM ex8 __attribute__((ext_vector_type(8)));
     constexpr int LPR = D / 8;        // lanes per row
     constexpr int RPB = 256 / LPR;    // rows per block and step
     const int tid = threadIdx.x;
     const int sub = tid % LPR;
     for (long long r = (long long)blockIdx.x * RPB + tid / LPR; r < p.n_rows; r += (long long)gridDim.x * RPB) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(p.d_o + r * D + 8 * sub);
-        const bf16x8 b = *reinterpret_cast<const bf16x8 *>(p.o + r * D + 8 * sub);
+        const ex8 a = *reinterpret_cast<const ex8 *>(reinterpret_cast<const ELEM *>(p.d_o) + r * D + 8 * sub);
+        const ex8 b = *reinterpret_cast<const ex8 *>(reinterpret_cast<const ELEM *>(p.o) + r * D + 8 * sub);
         float acc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e)

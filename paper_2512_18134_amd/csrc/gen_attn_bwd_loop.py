@@ -28,16 +28,20 @@ Hazards handled by construction (the assembler inserts no wait states):
   * back-to-back MFMAs never share an accumulator (S and dP alternate; the contraction walks its
     2*DB or DB accumulators round robin).
 
-usage: gen_attn_bwd_loop.py <kv|q> <D> <out.inc>
+usage: gen_attn_bwd_loop.py <kv|q> <D> <out.inc> [bf16|f16]
 """
 import os
 import sys
 
 
 class Gen:
-    def __init__(self, key_owner, D, NF=4, PFD=3):
-        assert D in (64, 128)
+    def __init__(self, key_owner, D, NF=4, PFD=3, dtype="bf16"):
+        assert D in (64, 128) and dtype in ("bf16", "f16")
         self.KO = key_owner
+        # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
+        self.dtype = dtype
+        self.mfma = "v_mfma_f32_32x32x16_" + dtype
+        self.cvt = "v_cvt_pk_%s_f32" % dtype
         self.D = D
         self.NW = 4
         self.BN = 32
@@ -169,11 +173,11 @@ class Gen:
             ch, db, st = a, b, c
             acc = self.ar(self.ACC + 16 * (st * self.DB + db), 16)
             src = DS_prev if st == 0 else P_prev      # set 0: dK^T (or dQ^T) from dS; set 1: dV^T from P
-            return "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (acc, f, self.vr(src + 4 * ch, 4), acc)
+            return "%s %s, %s, %s, %s" % (self.mfma, acc, f, self.vr(src + 4 * ch, 4), acc)
         ks, t = a, b
         dst = self.vr(S_nxt if t == 0 else DP_nxt, 16)
         own = self.ar((self.B1 if t == 0 else self.B2) + 4 * ks, 4)
-        return "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (dst, f, own, "0" if ks == 0 else dst)
+        return "%s %s, %s, %s, %s" % (self.mfma, dst, f, own, "0" if ks == 0 else dst)
 
     # ------------------------------------------------------------ VALU programs
     def aux(self, base, r):
@@ -197,8 +201,8 @@ class Gen:
             return ["v_mul_f32 v%d, v%d, v%d" % (DP_cur + 2 * k + i, S_cur + 2 * k + i, DP_cur + 2 * k + i)
                     for i in range(2)]
         def C(k):
-            return ["v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (P_new + k, S_cur + 2 * k, S_cur + 2 * k + 1),
-                    "v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (DS_new + k, DP_cur + 2 * k, DP_cur + 2 * k + 1)]
+            return ["%s v%d, v%d, v%d" % (self.cvt, P_new + k, S_cur + 2 * k, S_cur + 2 * k + 1),
+                    "%s v%d, v%d, v%d" % (self.cvt, DS_new + k, DP_cur + 2 * k, DP_cur + 2 * k + 1)]
         ops = []
         for t in range(8 + 2):
             if t < 8:
@@ -425,8 +429,9 @@ class Gen:
         self.generate()
         KS, DB = self.KS, self.DB
         out = []
-        out.append("// Generated by gen_attn_bwd_loop.py %s %d -- do not edit.  Main loop of attn_bwd_asm_kernel<%d, *, %s>."
-                   % ("kv" if self.KO else "q", self.D, self.D, "true" if self.KO else "false"))
+        out.append("// Generated by gen_attn_bwd_loop.py %s %d %s -- do not edit.  Main loop of attn_bwd_asm_kernel<%d, *, %s, %s>."
+                   % ("kv" if self.KO else "q", self.D, self.dtype, self.D, "true" if self.KO else "false",
+                      "true" if self.dtype == "f16" else "false"))
         out.append("// VGPRs used: %d, AGPRs used: %d.  MFMA slots per iteration: %d." % (self.NV, self.NA, self.NM))
         out.append("asm volatile(")
         for ln in self.lines:
@@ -486,6 +491,7 @@ if __name__ == "__main__":
     # ATTN_GEN_BWD_NF / ATTN_GEN_BWD_PFD (timing experiments): fragment buffers and prefetch distance
     nf = int(os.environ.get("ATTN_GEN_BWD_NF", "4"))
     pfd = int(os.environ.get("ATTN_GEN_BWD_PFD", "3"))
-    text = Gen(sys.argv[1] == "kv", int(sys.argv[2]), NF=nf, PFD=pfd).emit_inc()
+    dtype = sys.argv[4] if len(sys.argv) > 4 else "bf16"
+    text = Gen(sys.argv[1] == "kv", int(sys.argv[2]), NF=nf, PFD=pfd, dtype=dtype).emit_inc()
     with open(sys.argv[3], "w") as f:
         f.write(text)

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle.attn_oracle import attn_ref
+from oracle.attn_oracle import attn_bwd_ref, attn_ref
 from paper_2512_18134_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -128,3 +128,71 @@ def test_f16_rejects_what_it_does_not_cover(B):
     assert e.value.status == B.ATTN_ERR_SCALE
     with pytest.raises(TypeError):
         B.attn_fwd(q, q, q)            # the bf16 entry does not take fp16 tensors
+
+
+# ------------------------------------------------------------------ backward (attn_bwd_f16)
+BWD_TOL = 2.5e-3   # the bf16 bar (2e-2, relative to max(1, max |ref|) per tensor) / 8: three more significand bits
+
+
+def run_bwd(B, q, k, v, d_o, causal, scale):
+    qd, kd, vd, dod = to_dev(q), to_dev(k), to_dev(v), to_dev(d_o)
+    o, lse = B.attn_fwd_f16(qd, kd, vd, causal=causal, scale=scale)
+    nan = float("nan")
+    dq = torch.full(qd.shape, nan, dtype=torch.float16, device="cuda")
+    dk = torch.full(kd.shape, nan, dtype=torch.float16, device="cuda")
+    dv = torch.full(kd.shape, nan, dtype=torch.float16, device="cuda")
+    B.attn_bwd_f16(qd, kd, vd, o, dod, lse, dq, dk, dv, causal=causal, scale=scale)
+    torch.cuda.synchronize()
+    return [t.cpu().numpy().astype(np.float64) for t in (dq, dk, dv)]
+
+
+BWD_SMALL = [
+    (1, 1, 1, 300, 128, False),
+    (2, 2, 300, 431, 128, False),
+    (1, 3, 515, 515, 128, True),
+    (1, 2, 700, 100, 128, True),
+    (1, 2, 100, 700, 128, True),
+    (3, 5, 64, 64, 128, True),
+]
+
+
+@pytest.mark.parametrize("shape", BWD_SMALL, ids=lambda s: "bwd_B%d_H%d_Sq%d_Skv%d_D%d_%s" % (s[0], s[1], s[2], s[3], s[4], "causal" if s[5] else "full"))
+def test_bwd_small_shapes_elementwise(B, shape):
+    b, h, sq, skv, d, causal = shape
+    print("f16 bwd case", shape, flush=True)
+    q, k, v = synth.make_qkv(b, h, sq, skv, d, seed=900 + sq, dtype="f16")
+    d_o = synth.make_do(b, h, sq, d, seed=900 + sq, dtype="f16")
+    scale = synth.default_scale(d)
+    got = run_bwd(B, q, k, v, d_o, causal, scale)
+    want = attn_bwd_ref(q, k, v, d_o, causal, scale, dtype="f16")
+    for name, g, w in zip(("dq", "dk", "dv"), got, want):
+        assert np.all(np.isfinite(g)), name
+        err = np.max(np.abs(g - w)) / max(1.0, np.max(np.abs(w)))
+        print("%s %s rel. max error %.3e" % (shape, name, err), flush=True)
+        assert err <= BWD_TOL, (name, err)
+
+
+def test_bwd_paper_shape_heads_in_full(B):
+    # the shape of the paper's backward figures (BATCH=4, NUM_HEADS=32, HEAD_DIM=128, fp16, non-causal) at seq 2048
+    cfg = synth.paper_workload(2048, causal=False)
+    print("f16 bwd", cfg["name"], flush=True)
+    q, k, v = synth.make_qkv(cfg["B"], cfg["H"], cfg["S_q"], cfg["S_kv"], cfg["D"], cfg["seed"], dtype="f16")
+    d_o = synth.make_do(cfg["B"], cfg["H"], cfg["S_q"], cfg["D"], cfg["seed"], dtype="f16")
+    scale = synth.default_scale(cfg["D"])
+    got = run_bwd(B, q, k, v, d_o, False, scale)
+    heads = np.array([5, 126], dtype=np.int64)
+    want = attn_bwd_ref(q, k, v, d_o, False, scale, heads=heads, dtype="f16")
+    for name, g, w in zip(("dq", "dk", "dv"), got, want):
+        assert np.all(np.isfinite(g))
+        sub = g.reshape((-1,) + g.shape[2:])[heads]
+        err = np.max(np.abs(sub - w)) / max(1.0, np.max(np.abs(w)))
+        print("%s %s rel. max error %.3e" % (cfg["name"], name, err), flush=True)
+        assert err <= BWD_TOL
+
+
+def test_bwd_f16_rejects_what_it_does_not_cover(B):
+    z = torch.zeros((1, 1, 8, 64), dtype=torch.float16, device="cuda")
+    lse = torch.zeros((1, 1, 8), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.AttnError) as e:
+        B.attn_bwd_f16(z, z, z, z, z, lse)
+    assert e.value.status == B.ATTN_ERR_UNSUPPORTED_D
