@@ -44,7 +44,7 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
             return ATTN_ERR_LAUNCH;
     }
     int rc;
-    if constexpr (D == 128) {
+    if constexpr (D == 128 || D == 64) {
         // hand-scheduled key-owner sweep (needs scale > 0); ATTN_BWD_KERNEL=plain (debug only) keeps the
         // compiler-scheduled one
         static const bool plain = [] {
@@ -65,7 +65,7 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
     }
     if (rc != ATTN_OK)
         return rc;
-    if constexpr (D == 128) {
+    if constexpr (D == 128 || D == 64) {
         // hand-scheduled query-owner sweep; ATTN_BWD_KERNEL=plain (debug only) keeps the compiler-scheduled one
         static const bool plain_q = [] {
             const char *e = getenv("ATTN_BWD_KERNEL");

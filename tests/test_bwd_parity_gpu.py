@@ -167,28 +167,28 @@ def test_hand_scheduled_sweeps_equal_the_compiler_scheduled_ones(B, tmp_path):
         "import sys, numpy as np, torch; sys.path.insert(0, %r)\n"
         "from paper_2512_18134_amd import binding, synth\n"
         "res = {}\n"
-        "for causal in (False, True):\n"
-        "    q, k, v = synth.make_qkv(1, 2, 700, 650, 128, seed=23)\n"
-        "    d_o = synth.make_do(1, 2, 700, 128, seed=23)\n"
+        "for D, causal in ((128, False), (128, True), (64, True)):\n"
+        "    q, k, v = synth.make_qkv(1, 2, 700, 650, D, seed=23)\n"
+        "    d_o = synth.make_do(1, 2, 700, D, seed=23)\n"
         "    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)\n"
         "    qd, kd, vd, dod = dev(q), dev(k), dev(v), dev(d_o)\n"
         "    o, lse = binding.attn_fwd(qd, kd, vd, causal=causal)\n"
         "    g = binding.attn_bwd(qd, kd, vd, o, dod, lse, causal=causal)\n"
         "    torch.cuda.synchronize()\n"
         "    for n, t in zip(('dq', 'dk', 'dv'), g):\n"
-        "        res['%%s%%d' %% (n, causal)] = t.cpu().view(torch.int16).numpy()\n"
+        "        res['%%s%%d_%%d' %% (n, causal, D)] = t.cpu().view(torch.int16).numpy()\n"
         "np.savez(%r, **res)\n" % (root, out))
     env = dict(os.environ, ATTN_BWD_KERNEL="plain")
     subprocess.run([sys.executable, "-c", code], check=True, env=env, timeout=110)
     ref = np.load(out)
-    for causal in (False, True):
-        q, k, v = synth.make_qkv(1, 2, 700, 650, 128, seed=23)
-        d_o = synth.make_do(1, 2, 700, 128, seed=23)
-        got = run_gpu(B, q, k, v, d_o, causal, synth.default_scale(128))
+    for D, causal in ((128, False), (128, True), (64, True)):
+        q, k, v = synth.make_qkv(1, 2, 700, 650, D, seed=23)
+        d_o = synth.make_do(1, 2, 700, D, seed=23)
+        got = run_gpu(B, q, k, v, d_o, causal, synth.default_scale(D))
         for n, gt in zip(("dq", "dk", "dv"), got):
-            plain = synth.bf16_bits_to_f32(ref["%s%d" % (n, causal)].view(np.uint16)).astype(np.float64)
+            plain = synth.bf16_bits_to_f32(ref["%s%d_%d" % (n, causal, D)].view(np.uint16)).astype(np.float64)
             # same arithmetic up to fp32 re-association: within bf16 rounding of the gradients
-            assert np.max(np.abs(gt - plain)) <= 2.0 ** -6 * max(1.0, np.max(np.abs(plain))), (n, causal)
+            assert np.max(np.abs(gt - plain)) <= 2.0 ** -6 * max(1.0, np.max(np.abs(plain))), (n, causal, D)
 
 
 def test_rejected_arguments(B):
