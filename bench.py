@@ -121,7 +121,7 @@ def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops, host_qkv):
                    "D": cfg["D"], "causal": cfg["causal"], "flop_per_step": flops,
                    "kernel_ms_avg": float(np.mean(kern_ms)), "kernel_ms_min": float(np.min(kern_ms))},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg["name"] + "_bwd")},
     }
     if not args.no_cpu_baseline:
         to_bits = lambda t: t.cpu().view(torch.int16).numpy().view(np.uint16)
