@@ -7,8 +7,10 @@ Tolerances.  Every gradient element is a sum of products whose factors p and ds 
 to bf16 (relative 2^-9) and whose result is rounded to bf16 once more; Delta is computed from
 the bf16-rounded o.  With N(0,1) inputs the gradients have magnitude O(1) at most, and the
 accumulated error is dominated by the final rounding, half an ulp of the largest element.
-The bar used here: max |d - d_ref| <= 2e-2 * max(1, max |d_ref|) for each of dq, dk, dv (the
-forward bar of 2e-2 on O, made relative for tensors whose elements exceed 1).
+The bar used here: max |d - d_ref| <= 2e-2 * max |d_ref| + 2e-5 for each of dq, dk, dv: the forward bar of
+2e-2 on O (whose elements are O(1)) made relative to the size of the tensor, since gradients range from 1e-2
+(long sequences) to 50 (dV of a key every query attends to); the floor covers tensors that are exactly zero
+(one visible key: Delta is computed from the bf16-rounded o, so dq and dk come out ~1e-6 instead of 0).
 """
 import numpy as np
 import pytest
@@ -20,6 +22,7 @@ from paper_2512_18134_amd import synth
 pytestmark = pytest.mark.gpu
 
 TOL = 2e-2
+ABS_FLOOR = 2e-5
 
 
 @pytest.fixture(scope="module")
@@ -53,10 +56,11 @@ def compare(got, want, tag):
     worst = 0.0
     for name, g, w in zip(("dq", "dk", "dv"), got, want):
         assert np.all(np.isfinite(g)), (tag, name)
-        err = np.max(np.abs(g - w)) / max(1.0, np.max(np.abs(w)))
-        print("%s %s max|d|=%.3e (rel. to max(1,|ref|max=%.2f))" % (tag, name, err, np.max(np.abs(w))), flush=True)
-        assert err <= TOL, (tag, name, err)
-        worst = max(worst, err)
+        err = np.max(np.abs(g - w))
+        bar = TOL * np.max(np.abs(w)) + ABS_FLOOR
+        print("%s %s max|d|=%.3e (|ref|max=%.3f, bar %.3e)" % (tag, name, err, np.max(np.abs(w)), bar), flush=True)
+        assert err <= bar, (tag, name, err, bar)
+        worst = max(worst, err / bar)
     return worst
 
 
@@ -188,7 +192,22 @@ def test_hand_scheduled_sweeps_equal_the_compiler_scheduled_ones(B, tmp_path):
         for n, gt in zip(("dq", "dk", "dv"), got):
             plain = synth.bf16_bits_to_f32(ref["%s%d_%d" % (n, causal, D)].view(np.uint16)).astype(np.float64)
             # same arithmetic up to fp32 re-association: within bf16 rounding of the gradients
-            assert np.max(np.abs(gt - plain)) <= 2.0 ** -6 * max(1.0, np.max(np.abs(plain))), (n, causal, D)
+            assert np.max(np.abs(gt - plain)) <= 2.0 ** -6 * np.max(np.abs(plain)), (n, causal, D)
+
+
+def test_headline_shape_one_head_in_full(B):
+    # the forward headline workload's shape (B1 H16 S16384 D128, non-causal) in the launch configuration
+    # `bench.py --config 3 --bwd` times; the oracle computes one head in full (all 16384 rows of dq, dk, dv)
+    cfg, q, k, v, scale = synth.make_config(3)
+    print("bwd", cfg["name"], flush=True)
+    d_o = synth.make_do(cfg["B"], cfg["H"], cfg["S_q"], cfg["D"], cfg["seed"])
+    got = run_gpu(B, q, k, v, d_o, cfg["causal"], scale)
+    heads = np.array([11], dtype=np.int64)
+    want = attn_bwd_ref(q, k, v, d_o, cfg["causal"], scale, heads=heads)
+    sub = [g.reshape((-1,) + g.shape[2:])[heads] for g in got]
+    compare(sub, want, cfg["name"])
+    for g in got:
+        assert np.all(np.isfinite(g))
 
 
 def test_rejected_arguments(B):
