@@ -38,6 +38,7 @@ Hazards handled by construction (the assembler inserts no wait states):
 usage: gen_attn_loop.py <D> <out.inc> [bf16|f16]
 """
 import os
+import struct
 import sys
 
 
@@ -107,6 +108,13 @@ class Gen:
         self.lines = []
         # timing experiments only (results are wrong with any of these set): drop parts of the loop
         self.exp = set(filter(None, os.environ.get("ATTN_GEN_EXP", "").split(",")))
+
+    def tau_bits(self):
+        """Lazy-rescale threshold: P may reach 2^tau before the reference maximum moves (fp16 P must stay
+        below 2^15).  ATTN_GEN_TAU (timing experiments): 24 and 64 measured no faster than 8, also on
+        sharp-softmax inputs, whose running maximum jumps by far more than any threshold."""
+        tau = float(os.environ.get("ATTN_GEN_TAU", "8"))
+        return struct.unpack("<I", struct.pack("<f", tau))[0]
 
     # ------------------------------------------------------------------ helpers
     def e(self, s):
@@ -411,7 +419,7 @@ class Gen:
         e("s_nop 7")
         e("s_mov_b32 s%d, 0" % self.s_j)
         e("s_mov_b32 s%d, 0" % self.s_resc)
-        e("s_mov_b32 s%d, 0x41000000" % self.s_tau)            # 8.0: lazy-rescale threshold (log2 units)
+        e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, self.tau_bits()))   # lazy-rescale threshold (log2 units)
         e("s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kbase, 4 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kbase + 1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vbase, 2 * self.TB))

@@ -19,6 +19,8 @@ VGPRs.  K/V tiles: direct global->LDS loads, 4-stage rings, one barrier per tile
 
 usage: gen_attn_loop2.py <d128a|d256a> <out.inc>
 """
+import os
+import struct
 import sys
 
 CONFIGS = {
@@ -422,7 +424,7 @@ class Gen:
         e("s_nop 7")
         e("s_mov_b32 s%d, 0" % self.s_j)
         e("s_mov_b32 s%d, 0" % self.s_resc)
-        e("s_mov_b32 s%d, 0x41000000" % self.s_tau)
+        e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, struct.unpack("<I", struct.pack("<f", float(os.environ.get("ATTN_GEN_TAU", "8"))))[0]))
         e("s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kbase, 4 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kbase + 1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vbase, 2 * self.TB))
