@@ -16,7 +16,7 @@ change the bits.
 
 The paper's evaluation (Section 6.2) uses random FP16 inputs of shape
 (BATCH, NUM_HEADS, seq, HEAD_DIM); the five workloads here have the shapes and
-distributions the build's baseline file lists (bf16, iid N(0,1); the last one
+distributions of this library's benchmark set (bf16, iid N(0,1); the last one
 adds a per-row N(0, sigma=2) offset to Q and K, which makes the softmax sharp).
 """
 import numpy as np
@@ -100,7 +100,7 @@ def normal_bf16(seed, tensor_id, shape, row_offset_id=None, row_offset_sigma=0.0
     return out.reshape(shape)
 
 
-# The workloads (index = position in the baseline file's `configs`).
+# The five benchmark workloads (bench.py --config <index>; index 3 is the headline).
 CONFIGS = [
     dict(name="cfg0_B1_H1_S128_D64_full", B=1, H=1, S_q=128, S_kv=128, D=64, causal=False, seed=0, sharp=False),
     dict(name="cfg1_B4_H16_S1024_D64_full", B=4, H=16, S_q=1024, S_kv=1024, D=64, causal=False, seed=1, sharp=False),

@@ -1,6 +1,6 @@
 """Parity of the HIP path (through the C ABI) against the fp64 oracle.
 
-Tolerances (the build's stated bar): max |O_gpu - O_ref| <= 2e-2 (O is bf16),
+Tolerances: max |O_gpu - O_ref| <= 2e-2 (O is bf16),
 max |LSE_gpu - LSE_ref| <= 1e-3 (fp32, natural log).
 """
 import math
