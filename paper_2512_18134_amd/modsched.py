@@ -184,6 +184,49 @@ def normalise_costs(C, U):
     return best[1], best[2]
 
 
+# ------------------------------------------------------------------ memory capacity (Section 4.2)
+def duration(loop, v):
+    return max(1, len(loop.rrt[v]))
+
+
+def live_ranges(loop, M, I):
+    """[start, end) of the result of one instance of every instruction, in the time of its own iteration:
+    reserved from the cycle the instruction issues until its last consumer (u, delta) has finished, i.e.
+    cycle M[u] + I*delta + duration(u).  A result nobody consumes dies when its instruction finishes.
+    A loop-carried self edge (an accumulator updated in place: O += ...) hands its registers to the next
+    instance when that instance issues.  (The paper states liveness as backward dataflow constraints over
+    the unrolled schedule; for a fixed (M, I) those constraints have this closed form.)"""
+    out = {}
+    for v in M:
+        end = M[v] + duration(loop, v)
+        for u, w, d, delta in loop.edges:
+            if u == v and w == v:
+                end = max(end, M[v] + I * delta)
+            elif u == v:
+                end = max(end, M[w] + I * delta + duration(loop, w))
+        out[v] = (M[v], end)
+    return out
+
+
+def live_footprint(loop, M, I, footprint, resident=0):
+    """Steady-state memory use per cycle (mod I): sum over instructions of footprint x number of
+    overlapped iterations whose instance is live at that cycle, plus `resident` (loop invariants)."""
+    ranges = live_ranges(loop, M, I)
+    use = [resident] * I
+    for v, (a, b) in ranges.items():
+        f = footprint.get(v, 0)
+        if not f:
+            continue
+        for t in range(a, b):
+            use[t % I] += f
+    return use
+
+
+def fits(loop, M, I, footprint, capacity, resident=0):
+    """The paper's Memory Capacity constraint for one memory (here: the register file of a wave)."""
+    return max(live_footprint(loop, M, I, footprint, resident)) <= capacity
+
+
 # ------------------------------------------------------------------ the paper's running example
 def paper_toy():
     """Fig. 1: S = gemm(Q,K) on the tensor core, P = exp(S) on the exp unit, O += gemm(P,V) on the
@@ -227,6 +270,37 @@ def gfx950_attention(costs=GFX950_D128, U=24):
     return g, c, F
 
 
+# Registers per lane of the values in that graph (D = 128, 32 query rows per wave, 64-key tile): the
+# S block (two 32x32 fp32 accumulators), P packed to bf16, the O accumulators; the LDS fragments are
+# counted per buffer (4 registers) over the time they wait for their MFMA.  Loop invariants: Q fragments
+# (32), LDS/DMA addresses, masks, row state (~44 in the generated loop).
+GFX950_D128_REGS = {"QK": 32, "SM": 16, "PV": 64}
+GFX950_D128_RESIDENT = 32 + 16 + 44       # Q + fragment ring + addresses and state
+
+
+def gfx950_backward_key_owner(U=24):
+    """Tile-level graph of the key-owner backward sweep (one wave, 32 keys, 32-query tile): S and dP on the
+    matrix pipe, the element-wise work on the VALU, the two contractions on the matrix pipe; dK/dV carry."""
+    # measured per-wave costs in matrix-pipe cycles: 16 MFMAs for S+dP, 16 for the contractions, ~80 VALU ops
+    names = ["SDP", "EW", "CON"]
+    Cn, F = normalise_costs([512, 480, 512], U)
+    c = dict(zip(names, Cn))
+    g = Loop({"MFMA": 1, "VALU": 1})
+    g.op("SDP", "MFMA", c["SDP"])
+    g.op("EW", "VALU", c["EW"])
+    g.op("CON", "MFMA", c["CON"])
+    g.dep("SDP", "EW")
+    g.dep("EW", "CON")
+    g.dep("CON", "CON", delta=1)
+    return g, c, F
+
+
+# S and dP (16 + 16), P and dS packed (8 + 8), dK^T and dV^T accumulators (64 + 64); resident: the owner's
+# K and V rows as B operands (64), LSE'/Delta of the tile (32), fragment ring (16), addresses and state (~56)
+GFX950_BWD_REGS = {"SDP": 32, "EW": 16, "CON": 128}
+GFX950_BWD_RESIDENT = 64 + 32 + 16 + 56
+
+
 if __name__ == "__main__":
     g = paper_toy()
     M, I, L = schedule(g)
@@ -236,3 +310,9 @@ if __name__ == "__main__":
     print("gfx950 D=128 wave: normalised costs %s (F=%d)" % (c, F))
     print("  I=%d (MFMA-bound: %d)  L=%d  stages=%d  M=%s" % (I, c["QK"] + c["PV"], L, math.ceil(L / I), M))
     print("  in-order interval=%d  => pipelining gain %.2fx" % (in_order_interval(g), in_order_interval(g) / I))
+    print("  registers live in the steady state: max %d of 256 (two waves per SIMD)" %
+          max(live_footprint(g, M, I, GFX950_D128_REGS, GFX950_D128_RESIDENT)))
+    g, c, F = gfx950_backward_key_owner()
+    M, I, L = schedule(g, max_len=4 * sum(c.values()))
+    print("gfx950 backward key-owner wave: I=%d L=%d stages=%d, registers max %d (one wave per SIMD: 512)" %
+          (I, L, math.ceil(L / I), max(live_footprint(g, M, I, GFX950_BWD_REGS, GFX950_BWD_RESIDENT))))

@@ -70,3 +70,54 @@ def test_gfx950_attention_is_matrix_pipe_bound_with_three_stages():
     # the schedule spans three intervals (QK of tile j+1, softmax of j, PV of j-1 overlap)
     assert math.ceil(L / I) == 3
     assert ms.in_order_interval(g) >= 2 * I - 2
+
+
+def test_memory_capacity_on_the_running_example():
+    # Section 4.2 on Fig. 1: S lives until P has executed, P until O has, O is an accumulator updated in place
+    g = ms.paper_toy()
+    M, I = {"S": 0, "P": 2, "O": 3}, 2
+    assert ms.live_ranges(g, M, I) == {"S": (0, 3), "P": (2, 4), "O": (3, 5)}
+    # steady state, cycle 0: the new S, the previous iteration's S (P reads it now), that P (being written)
+    # and O; cycle 1: S, P (O reads it now) and O
+    use = ms.live_footprint(g, M, I, {"S": 1, "P": 1, "O": 1})
+    assert use == [4, 3]
+    assert ms.fits(g, M, I, {"S": 1, "P": 1, "O": 1}, capacity=4)
+    assert not ms.fits(g, M, I, {"S": 1, "P": 1, "O": 1}, capacity=3)
+    # the program-order loop peaks one lower: pipelining costs memory (the trade the paper's Section 6.3
+    # finds decisive for the backward pass on Hopper)
+    seq = {"S": 0, "P": 1, "O": 2}
+    assert ms.live_footprint(g, seq, 3, {"S": 1, "P": 1, "O": 1}) == [2, 3, 2]
+
+
+def _load_generator(name):
+    import importlib.util
+    import os
+    path = os.path.join(os.path.dirname(ms.__file__), "csrc", name + ".py")
+    spec = importlib.util.spec_from_file_location(name, path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod
+
+
+def test_register_demand_matches_what_the_generators_allocate():
+    # forward, D = 128: the three-stage schedule keeps two S blocks and two P blocks alive at times; with
+    # the loop invariants that fits the 256 registers of a wave at two waves per SIMD
+    g, c, _ = ms.gfx950_attention(U=24)
+    M, I, L = ms.schedule(g, max_len=4 * sum(c.values()))
+    ranges = ms.live_ranges(g, M, I)
+    assert ranges["QK"][1] - ranges["QK"][0] > I       # S(j+1) is produced while S(j) is still being read
+    assert ranges["SM"][1] - ranges["SM"][0] > I       # P(j) is produced while P(j-1) is still being read
+    peak = max(ms.live_footprint(g, M, I, ms.GFX950_D128_REGS, ms.GFX950_D128_RESIDENT))
+    gen = _load_generator("gen_attn_loop").Gen(128)
+    # the generator double-buffers S and P statically and allocates exactly what the model's values need
+    assert gen.SB - gen.SA == 32 and gen.PB - gen.PA == 16
+    static = 2 * 32 + 2 * 16 + 64 + ms.GFX950_D128_RESIDENT
+    assert peak <= static <= 256 and abs(gen.NV - static) <= 8
+    # the backward key-owner sweep: accumulators for dK and dV plus the owner's rows do not fit 256,
+    # so it runs one wave per SIMD (512 registers, the accumulators in AGPRs)
+    g, c, _ = ms.gfx950_backward_key_owner()
+    M, I, L = ms.schedule(g, max_len=4 * sum(c.values()))
+    peak_b = max(ms.live_footprint(g, M, I, ms.GFX950_BWD_REGS, ms.GFX950_BWD_RESIDENT))
+    assert 256 < peak_b <= 512
+    genb = _load_generator("gen_attn_bwd_loop").Gen(True, 128)
+    assert abs((genb.NV + genb.NA) - (2 * 32 + 2 * 16 + 128 + ms.GFX950_BWD_RESIDENT)) <= 8
