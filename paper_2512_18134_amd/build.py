@@ -24,9 +24,10 @@ def generate_sources(verbose=False):
     gen = os.path.join(HERE, "csrc", "gen_attn_loop.py")
     out_dir = os.path.join(HERE, "csrc", "generated")
     os.makedirs(out_dir, exist_ok=True)
-    for d, dtype in ((64, "bf16"), (128, "bf16"), (64, "f16"), (128, "f16")):
-        out = os.path.join(out_dir, "attn_loop_d%d%s.inc" % (d, "" if dtype == "bf16" else "_" + dtype))
-        cmd = [sys.executable, gen, str(d), out, dtype]
+    for d, dtype, nw in ((64, "bf16", 8), (128, "bf16", 8), (64, "f16", 8), (128, "f16", 8), (64, "bf16", 4)):
+        out = os.path.join(out_dir, "attn_loop_d%d%s%s.inc" % (d, "" if dtype == "bf16" else "_" + dtype,
+                                                               "" if nw == 8 else "_w%d" % nw))
+        cmd = [sys.executable, gen, str(d), out, dtype, str(nw)]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

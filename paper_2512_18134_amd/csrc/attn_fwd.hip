@@ -17,6 +17,8 @@ namespace {
 
 using attn::Params;
 
+constexpr int kW4MaxKeys = 4096;  // D = 64, causal: up to this many keys the 4-wave workgroups win (measured)
+
 // opt in to more than 64 KB of dynamic LDS when a kernel needs it (gfx950 has 160 KB per CU)
 template <typename K>
 bool allow_lds(K kern, int bytes)
@@ -67,6 +69,22 @@ template <int D>
 int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
 {
     constexpr int LDS = 8 * 64 * D * 2;
+    if constexpr (D == 64) {
+        // Debug only: ATTN_FWD_W4=0 / 1 forces 8-wave / 4-wave workgroups.
+        static const int w4 = [] {
+            const char *e = getenv("ATTN_FWD_W4");
+            return e ? atoi(e) : -1;
+        }();
+        // Measured: two 4-wave workgroups per CU instead of one 8-wave one change little when every
+        // workgroup streams the same number of tiles (-3 % at long S, +-2 % at short S); with a causal mask
+        // and few tiles the finer query tiles balance better (+13 % at S = 1024, +4 % at S = 4096).
+        const bool use4 = w4 >= 0 ? w4 != 0 : (causal && p.S_kv <= kW4MaxKeys);
+        if (use4) {
+            if (causal)
+                return launch(attn::attn_fwd_asm_kernel<64, true, false, false, 4>, p, BH, 128, 256, LDS, stream);
+            return launch(attn::attn_fwd_asm_kernel<64, false, false, false, 4>, p, BH, 128, 256, LDS, stream);
+        }
+    }
     if (causal)
         return launch(attn::attn_fwd_asm_kernel<D, true>, p, BH, 256, 512, LDS, stream);
     return launch(attn::attn_fwd_asm_kernel<D, false>, p, BH, 256, 512, LDS, stream);

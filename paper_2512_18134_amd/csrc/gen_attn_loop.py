@@ -35,7 +35,7 @@ Hazards handled by construction (the assembler inserts no wait states):
     replaying the instruction stream (including the reads prefetched for the
     next iteration).
 
-usage: gen_attn_loop.py <D> <out.inc> [bf16|f16]
+usage: gen_attn_loop.py <D> <out.inc> [bf16|f16] [waves per workgroup: 8|4]
 """
 import os
 import struct
@@ -43,8 +43,9 @@ import sys
 
 
 class Gen:
-    def __init__(self, D, NF=4, PFD=3, dtype="bf16"):
-        assert D in (64, 128) and dtype in ("bf16", "f16")
+    def __init__(self, D, NF=4, PFD=3, dtype="bf16", NW=8):
+        assert D in (64, 128) and dtype in ("bf16", "f16") and NW in (4, 8)
+        self.NW = NW                      # waves per workgroup: every wave loads 1/NW of each K/V tile
         self.D = D
         self.dtype = dtype
         # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
@@ -54,7 +55,7 @@ class Gen:
         self.DB = D // 32
         self.ROWB = 2 * D
         self.TB = 64 * self.ROWB
-        self.NLD = self.TB // 8192
+        self.NLD = self.TB // (NW * 1024)
         self.NSTG = 4
         self.NF, self.PFD = NF, PFD
         self.NPV = 4 * self.DB
@@ -236,7 +237,7 @@ class Gen:
             if "nodma" in self.exp:
                 out.append([])
                 continue
-            out.append(["s_add_u32 m0, s%d, %d" % (lds, stage * self.TB + i * 8192),
+            out.append(["s_add_u32 m0, s%d, %d" % (lds, stage * self.TB + i * self.NW * 1024),
                         "s_nop 0",
                         "global_load_lds_dwordx4 v%d, %s" % (self.DVOFF + i, self.sr(ptr, 2))])
         return out
@@ -255,7 +256,7 @@ class Gen:
             self.e("v_min_i32 v%d, s%d, v%d" % (t, self.s_skvm1, t))
             self.e("v_lshlrev_b32 v%d, %d, v%d" % (t, sh, t))
             self.e("v_add_u32 v%d, v%d, v%d" % (t, t, self.DCH + i))
-            self.e("s_add_u32 m0, s%d, %d" % (lds, stage * self.TB + i * 8192))
+            self.e("s_add_u32 m0, s%d, %d" % (lds, stage * self.TB + i * self.NW * 1024))
             self.e("s_nop 0")
             self.e("global_load_lds_dwordx4 v%d, %s" % (t, self.sr(base, 2)))
         self.e("s_branch %s" % ret)
@@ -512,6 +513,7 @@ class Gen:
 if __name__ == "__main__":
     D = int(sys.argv[1])
     dtype = sys.argv[3] if len(sys.argv) > 3 else "bf16"
-    text = Gen(D, PFD=int(os.environ.get("ATTN_GEN_PFD", "3")), dtype=dtype).emit_inc()
+    nw = int(sys.argv[4]) if len(sys.argv) > 4 else 8
+    text = Gen(D, PFD=int(os.environ.get("ATTN_GEN_PFD", "3")), dtype=dtype, NW=nw).emit_inc()
     with open(sys.argv[2], "w") as f:
         f.write(text)
