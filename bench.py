@@ -138,6 +138,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="index into the baseline configs (3 = headline D=128 S=16384)")
     ap.add_argument("--paper-seq", type=int, default=0,
                     help="time the paper's Section 6.2 shape (B=4, H=32, D=128, non-causal) at this sequence length")
+    ap.add_argument("--causal", action="store_true", help="with --paper-seq: the causal variant of that shape")
     ap.add_argument("--dtype", choices=["bf16", "f16"], default=None,
                     help="element type (default: bf16 for --config, f16 for --paper-seq)")
     ap.add_argument("--bwd", action="store_true",
@@ -182,7 +183,7 @@ def main():
         scale = synth.default_scale(cfg["D"])
         q = k = v = None
     elif args.paper_seq:
-        cfg = synth.paper_workload(args.paper_seq, causal=False)
+        cfg = synth.paper_workload(args.paper_seq, causal=args.causal)
         cfg["dtype"] = args.dtype or "f16"
         cfg["name"] = cfg["name"].replace("_f16", "_" + cfg["dtype"])
         tdt = torch.float16 if cfg["dtype"] == "f16" else torch.bfloat16

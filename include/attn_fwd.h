@@ -117,6 +117,16 @@ int attn_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float
 /* Bytes of workspace attn_fwd_splitkv needs: n_split * B * H * S_q * (D + 1) * 4; -1 on invalid arguments. */
 long long attn_fwd_splitkv_workspace_bytes(int B, int H, int S_q, int D, int n_split);
 
+/*
+ * Diagnostic, host only (no GPU call): which (head, tile) the workgroup with id `workgroup` of a launch of
+ * n_heads * n_tiles workgroups works on -- the work decomposition of the kernels (XCD-aware; causal:
+ * heaviest tiles first, in groups of heads that share an L2).  `*head` = b*H + h, `*tile` = index of the
+ * tile of owner rows (query tiles in the forward pass; the key-owner backward sweep counts its tiles from
+ * the other end).  Returns ATTN_OK, or ATTN_ERR_NULL / ATTN_ERR_SHAPE (n_heads, n_tiles < 1, product above
+ * 2^31 - 1, workgroup outside [0, n_heads * n_tiles)).
+ */
+int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, int *head, int *tile);
+
 /* Static, NUL-terminated description of an attn_status value; never freed. */
 const char *attn_strerror(int status);
 

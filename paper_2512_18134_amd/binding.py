@@ -34,6 +34,8 @@ _lib.attn_strerror.restype = ctypes.c_char_p
 _lib.attn_strerror.argtypes = [ctypes.c_int]
 _lib.attn_version.restype = ctypes.c_int
 _lib.attn_version.argtypes = []
+_lib.attn_workgroup_tile.restype = ctypes.c_int
+_lib.attn_workgroup_tile.argtypes = [ctypes.c_int] * 4 + [ctypes.POINTER(ctypes.c_int)] * 2
 
 ATTN_OK = 0
 ATTN_ERR_NULL = -1
@@ -58,6 +60,16 @@ def attn_strerror(status):
 
 def attn_version():
     return int(_lib.attn_version())
+
+
+def attn_workgroup_tile(causal, workgroup, n_heads, n_tiles):
+    """attn_workgroup_tile (host-only diagnostic): the (head, tile) that workgroup id works on."""
+    head, tile = ctypes.c_int(-1), ctypes.c_int(-1)
+    rc = int(_lib.attn_workgroup_tile(int(bool(causal)), int(workgroup), int(n_heads), int(n_tiles),
+                                      ctypes.byref(head), ctypes.byref(tile)))
+    if rc != ATTN_OK:
+        raise AttnError(rc)
+    return head.value, tile.value
 
 
 def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S_q, S_kv, D, causal, scale, stream_ptr):

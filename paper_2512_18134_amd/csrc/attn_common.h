@@ -45,12 +45,15 @@ __device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 *
 // workgroup id -> logical id such that every XCD owns a contiguous range of
 // logical ids (all query tiles of a head then share one XCD's L2 while they
 // stream the same K/V).
-__device__ __forceinline__ int xcd_remap(int wid, int total)
+__host__ __device__ __forceinline__ int xcd_remap(int wid, int total)
 {
     const int per = total / kNumXcd, rem = total % kNumXcd;
     const int xcd = wid % kNumXcd, slot = wid / kNumXcd;
     return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + slot;
 }
+
+// Causal launches: workgroups per XCD that are handed out as one heaviest-first group (2 per CU).
+constexpr int kCausalGroupWgs = 64;
 
 // Kernel parameters (plain struct, passed by value).
 struct Params {
@@ -72,12 +75,16 @@ struct Params {
 // Workgroup id -> (batch*head, query tile).
 //  * not causal: all tiles cost the same; every XCD takes a contiguous range of (bh, qt) pairs.
 //  * causal: query tile qt streams ~(qt + 1) times as many K/V tiles as tile 0, and a CU holds one
-//    workgroup at a time, so the dispatch order decides the balance: each XCD hands out its tiles
-//    heaviest first ACROSS its heads (a CU that finishes a light tile of the first batch then picks up
-//    the heaviest one left).  With B*H a multiple of the XCD count every XCD owns whole heads (K/V stay
-//    in one L2); otherwise the order is heaviest-first over the whole grid.
+//    workgroup at a time, so the dispatch order decides the balance: tiles are handed out heaviest
+//    first (a CU that finishes a light tile of the first batch then picks up the heaviest one left).
+//    With B*H a multiple of the XCD count every XCD owns whole heads (K/V stay in one L2) and works
+//    through them in groups of just enough heads for 64 workgroups -- two per CU of the XCD, so that
+//    heavy and light tiles pair up -- heaviest first across the heads of a group: the workgroups in
+//    flight on an XCD then stream the K/V of one or two heads, not of every head the XCD owns, and
+//    keep hitting its L2.  Otherwise the tiles of a head go to all XCDs and the order is heaviest
+//    first over the whole grid (chip-wide groups of heads measured no better there).
 template <bool CAUSAL>
-__device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int n_t, int &bh, int &t)
+__host__ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int n_t, int &bh, int &t)
 {
     if (!CAUSAL) {
         const int logical = xcd_remap(wid, total_wg);
@@ -88,8 +95,13 @@ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int n_t, int
     const int n_bh = total_wg / n_t;
     if (n_bh % kNumXcd == 0) {
         const int nh = n_bh / kNumXcd, xcd = wid % kNumXcd, i = wid / kNumXcd;
-        t = n_t - 1 - i / nh;
-        bh = xcd * nh + i % nh;
+        const int want = (kCausalGroupWgs + n_t - 1) / n_t;
+        const int gsz = want < nh ? want : nh;  // heads per group
+        const int grp = i / (gsz * n_t), j = i % (gsz * n_t);
+        const int left = nh - grp * gsz;
+        const int gh = left < gsz ? left : gsz;  // the last group may be short
+        t = n_t - 1 - j / gh;
+        bh = xcd * nh + grp * gsz + j % gh;
     } else {
         t = n_t - 1 - wid / n_bh;
         bh = wid % n_bh;

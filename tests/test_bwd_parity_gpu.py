@@ -210,6 +210,22 @@ def test_headline_shape_one_head_in_full(B):
         assert np.all(np.isfinite(g))
 
 
+def test_causal_heads_dispatched_in_groups(B):
+    # a causal launch whose XCDs each own three heads and take them in groups (two heads, then one):
+    # both sweeps must still cover every owner tile of every head; two heads against the oracle in full
+    b, h, s, d = 1, 24, 4200, 128
+    print("bwd grouped causal", (b, h, s, d), flush=True)
+    q, k, v = synth.make_qkv(b, h, s, s, d, seed=71)
+    d_o = synth.make_do(b, h, s, d, seed=71)
+    scale = synth.default_scale(d)
+    got = run_gpu(B, q, k, v, d_o, True, scale)
+    for g in got:
+        assert np.all(np.isfinite(g))
+    heads = np.array([1, 23], dtype=np.int64)       # first group of XCD 0, short last group of XCD 7
+    want = attn_bwd_ref(q, k, v, d_o, True, scale, heads=heads)
+    compare([g.reshape((-1,) + g.shape[2:])[heads] for g in got], want, "grouped causal")
+
+
 def test_rejected_arguments(B):
     z = torch.zeros((1, 1, 8, 256), dtype=torch.bfloat16, device="cuda")
     lse = torch.zeros((1, 1, 8), dtype=torch.float32, device="cuda")
