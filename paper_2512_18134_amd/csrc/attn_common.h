@@ -77,12 +77,11 @@ struct Params {
 //  * causal: query tile qt streams ~(qt + 1) times as many K/V tiles as tile 0, and a CU holds one
 //    workgroup at a time, so the dispatch order decides the balance: tiles are handed out heaviest
 //    first (a CU that finishes a light tile of the first batch then picks up the heaviest one left).
-//    With B*H a multiple of the XCD count every XCD owns whole heads (K/V stay in one L2) and works
-//    through them in groups of just enough heads for 64 workgroups -- two per CU of the XCD, so that
-//    heavy and light tiles pair up -- heaviest first across the heads of a group: the workgroups in
-//    flight on an XCD then stream the K/V of one or two heads, not of every head the XCD owns, and
-//    keep hitting its L2.  Otherwise the tiles of a head go to all XCDs and the order is heaviest
-//    first over the whole grid (chip-wide groups of heads measured no better there).
+//    Every XCD owns whole heads (K/V stay in one L2) and works through them in groups of enough
+//    heads for at least 64 workgroups -- two per CU of the XCD, so that heavy and light tiles pair up --
+//    heaviest first across the heads of a group: the workgroups in flight on an XCD then stream the
+//    K/V of one or two heads, not of every head the XCD owns, and keep hitting its L2.  When B*H is
+//    not a multiple of the XCD count, the heads left over are shared out tile by tile first.
 template <bool CAUSAL>
 __host__ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int n_t, int &bh, int &t)
 {
@@ -92,20 +91,41 @@ __host__ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int
         t = logical % n_t;
         return;
     }
+    // XCD x owns `a` whole heads (x*a .. x*a + a - 1); the r = n_bh % 8 heads left over are dealt
+    // to the XCDs tile by tile, heaviest first in alternating direction (so that every XCD gets the
+    // same weight), and head the XCD's queue.
     const int n_bh = total_wg / n_t;
-    if (n_bh % kNumXcd == 0) {
-        const int nh = n_bh / kNumXcd, xcd = wid % kNumXcd, i = wid / kNumXcd;
-        const int want = (kCausalGroupWgs + n_t - 1) / n_t;
-        const int gsz = want < nh ? want : nh;  // heads per group
-        const int grp = i / (gsz * n_t), j = i % (gsz * n_t);
-        const int left = nh - grp * gsz;
-        const int gh = left < gsz ? left : gsz;  // the last group may be short
-        t = n_t - 1 - j / gh;
-        bh = xcd * nh + grp * gsz + j % gh;
-    } else {
-        t = n_t - 1 - wid / n_bh;
-        bh = wid % n_bh;
+    const int a = n_bh / kNumXcd, r = n_bh % kNumXcd;
+    const int xcd = wid % kNumXcd;
+    int i = wid / kNumXcd;
+    const int n_left = r * n_t;                                  // tiles of the left-over heads
+    const int m_x = (n_left - xcd + kNumXcd - 1) / kNumXcd;      // ... that reach this XCD
+    if (i < m_x) {
+        const bool back = (i & 1) && kNumXcd * (i + 1) <= n_left;  // odd full rows run 7..0
+        const int e = kNumXcd * i + (back ? kNumXcd - 1 - xcd : xcd);
+        t = n_t - 1 - e / r;
+        bh = kNumXcd * a + e % r;
+        return;
     }
+    i -= m_x;
+    // groups of at least `want` heads (64 workgroups), sizes as even as possible, larger ones first:
+    // a short group at the end of the queue would leave its heavy tiles without light partners
+    const int want = (kCausalGroupWgs + n_t - 1) / n_t;
+    const int ng = a > want ? a / want : 1;
+    const int base = a / ng, extra = a % ng;     // `extra` groups of base + 1 heads, then groups of base
+    const int big = extra * (base + 1) * n_t;
+    int gh, head0, j;
+    if (i < big) {
+        gh = base + 1;
+        head0 = i / (gh * n_t) * gh;
+        j = i % (gh * n_t);
+    } else {
+        gh = base;
+        head0 = extra * (base + 1) + (i - big) / (gh * n_t) * gh;
+        j = (i - big) % (gh * n_t);
+    }
+    t = n_t - 1 - j / gh;
+    bh = xcd * a + head0 + j % gh;
 }
 
 template <bool CAUSAL>
