@@ -2,7 +2,8 @@
 
 The hand-picked shapes of the other GPU tests cover the tile boundaries that were thought of; these
 cover the ones that were not: 48 shapes with B in 1..3, H in 1..4, S_q and S_kv in 1..700
-(a quarter of them forced to a multiple of 32 plus or minus one), D in {64, 128, 256}, causal or not.
+(a quarter of them forced to a multiple of 32 plus or minus one), D in {64, 128, 256}, causal or not,
+and 12 with many heads (B in 1..8, H in 1..16) on sequences of at most 330, mostly causal.
 Bars as in the per-entry tests.
 """
 import numpy as np
@@ -36,7 +37,18 @@ def shapes(n, seed):
     return out
 
 
-SHAPES = shapes(48, seed=2024)
+def many_heads(n, seed):
+    # B*H up to 128 on short sequences: every XCD owns several heads (the causal dispatch order
+    # then works through them in groups; left-over heads are shared out tile by tile)
+    rng = np.random.default_rng(seed)
+    out = []
+    for i, s in enumerate(shapes(n, seed)):
+        out.append((int(rng.integers(1, 9)), int(rng.integers(1, 17)), min(s[2], 330), min(s[3], 330), s[4],
+                    i % 4 != 3, 2000 + i))
+    return out
+
+
+SHAPES = shapes(48, seed=2024) + many_heads(12, seed=2025)
 
 
 def dev(bits, dt):
