@@ -211,9 +211,6 @@ def main():
 
     stream = torch.cuda.current_stream(dev)
     if args.bwd:
-        if cfg["dtype"] == "f16" and cfg["D"] != 128:
-            print("bench.py: --bwd in fp16 needs D = 128", file=sys.stderr)
-            sys.exit(2)
         return bench_bwd(args, cfg, qd, kd, vd, scale, stream, flops, (q, k, v))
     if args.splitkv:
         ws = torch.empty((binding.attn_fwd_splitkv_workspace_bytes(cfg["B"], cfg["H"], cfg["S_q"], cfg["D"], args.splitkv),),

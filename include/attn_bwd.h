@@ -58,9 +58,8 @@ int attn_bwd(const void *q, const void *k, const void *v, const void *o, const v
 /*
  * attn_bwd_f16 -- the same operation on IEEE fp16 tensors (q, k, v, o, d_o, dq, dk, dv), the element
  * type of the paper's Section 6.3 backward figures; pairs with attn_fwd_f16.  Arguments, layout,
- * ownership and error behaviour are those of attn_bwd, except: D must be 128 (other values return
- * ATTN_ERR_UNSUPPORTED_D) and scale must be > 0 (0 returns ATTN_ERR_SCALE).  p and ds are rounded
- * to fp16 before the products that consume them.
+ * ownership and error behaviour are those of attn_bwd (D 64 or 128), except: scale must be > 0
+ * (0 returns ATTN_ERR_SCALE).  p and ds are rounded to fp16 before the products that consume them.
  */
 int attn_bwd_f16(const void *q, const void *k, const void *v, const void *o, const void *d_o,
                  const float *lse, void *dq, void *dk, void *dv, float *delta_ws,

@@ -148,7 +148,7 @@ def attn_bwd_f16_raw(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr
 
 def attn_bwd_f16(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, causal=False, scale=None,
                  stream=None):
-    """attn_bwd_f16 on torch device tensors: as attn_bwd, with fp16 tensors (D = 128)."""
+    """attn_bwd_f16 on torch device tensors: as attn_bwd, with fp16 tensors."""
     import torch
     return _marshal_bwd(attn_bwd_f16_raw, torch.float16, q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, causal, scale,
                         stream)

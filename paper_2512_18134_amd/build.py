@@ -40,7 +40,7 @@ def generate_sources(verbose=False):
         subprocess.run(cmd, check=True)
     gen3 = os.path.join(HERE, "csrc", "gen_attn_bwd_loop.py")
     for kind, d, dtype in (("kv", 128, "bf16"), ("q", 128, "bf16"), ("kv", 128, "f16"), ("q", 128, "f16"),
-                           ("kv", 64, "bf16"), ("q", 64, "bf16")):
+                           ("kv", 64, "bf16"), ("q", 64, "bf16"), ("kv", 64, "f16"), ("q", 64, "f16")):
         out = os.path.join(out_dir, "attn_bwd_loop_%s_d%d%s.inc" % (kind, d, "" if dtype == "bf16" else "_" + dtype))
         cmd = [sys.executable, gen3, kind, str(d), out, dtype]
         if verbose:

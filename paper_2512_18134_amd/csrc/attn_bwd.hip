@@ -148,6 +148,25 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     return D == 64 ? launch_bwd<64, 8>(p, (int)BH, causal, st) : launch_bwd<128, 8>(p, (int)BH, causal, st);
 }
 
+template <int D>
+static int launch_bwd_f16(const BwdParams &p, int BH, int causal, hipStream_t st)
+{
+    {
+        const long long blocks = (p.n_rows + 15) / 16;
+        const unsigned grid = (unsigned)(blocks < 4096 ? blocks : 4096);
+        hipLaunchKernelGGL((attn::attn_bwd_delta_kernel<D, _Float16>), dim3(grid), dim3(256), 0, st, p);
+        if (hipGetLastError() != hipSuccess)
+            return ATTN_ERR_LAUNCH;
+    }
+    constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
+    const int rk = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true, true>, p, BH, p.S_kv, 4, LDSA, st)
+                          : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true, true>, p, BH, p.S_kv, 4, LDSA, st);
+    if (rk != ATTN_OK)
+        return rk;
+    return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false, true>, p, BH, p.S_q, 4, LDSA, st)
+                  : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false, true>, p, BH, p.S_q, 4, LDSA, st);
+}
+
 extern "C" int attn_bwd_f16(const void *q, const void *k, const void *v, const void *o, const void *d_o,
                             const float *lse, void *dq, void *dk, void *dv, float *delta_ws, int B, int H, int S_q,
                             int S_kv, int D, int causal, float scale, void *stream)
@@ -157,24 +176,8 @@ extern "C" int attn_bwd_f16(const void *q, const void *k, const void *v, const v
     if (rc != ATTN_OK)
         return rc;
     // fp16 runs on the hand-scheduled sweeps only
-    if (D != 128)
-        return ATTN_ERR_UNSUPPORTED_D;
     if (!(scale > 0.f))
         return ATTN_ERR_SCALE;
-    const int BH = B * H;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    {
-        const long long blocks = (p.n_rows + 15) / 16;
-        const unsigned grid = (unsigned)(blocks < 4096 ? blocks : 4096);
-        hipLaunchKernelGGL((attn::attn_bwd_delta_kernel<128, _Float16>), dim3(grid), dim3(256), 0, st, p);
-        if (hipGetLastError() != hipSuccess)
-            return ATTN_ERR_LAUNCH;
-    }
-    constexpr int LDSA = 2 * 6 * 32 * 128 * 2 + 6 * 256;
-    const int rk = causal ? launch_sweep(attn::attn_bwd_asm_kernel<128, true, true, true>, p, BH, S_kv, 4, LDSA, st)
-                          : launch_sweep(attn::attn_bwd_asm_kernel<128, false, true, true>, p, BH, S_kv, 4, LDSA, st);
-    if (rk != ATTN_OK)
-        return rk;
-    return causal ? launch_sweep(attn::attn_bwd_asm_kernel<128, true, false, true>, p, BH, S_q, 4, LDSA, st)
-                  : launch_sweep(attn::attn_bwd_asm_kernel<128, false, false, true>, p, BH, S_q, 4, LDSA, st);
+    return D == 64 ? launch_bwd_f16<64>(p, B * H, causal, st) : launch_bwd_f16<128>(p, B * H, causal, st);
 }

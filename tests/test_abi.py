@@ -131,14 +131,14 @@ def test_bwd_entry_validates_before_any_launch(binding):
     for s in (float("nan"), float("inf"), -1.0):
         assert f(scale=s) == b.ATTN_ERR_SCALE
     assert f(S_q=1 << 24, D=128) == b.ATTN_ERR_SHAPE
-    # the fp16 entry: same checks, then D = 128 and scale > 0 only
+    # the fp16 entry: same checks, and scale > 0 only
     def h(**kw):
         ptrs = [kw.get(n, ok) for n in names]
         rest = [kw.get(n, d) for n, d in (("B", 1), ("H", 1), ("S_q", 8), ("S_kv", 8), ("D", 128), ("causal", 0),
                                            ("scale", 0.125), ("stream", 0))]
         return b.attn_bwd_f16_raw(*(ptrs + rest))
     assert h(q=0) == b.ATTN_ERR_NULL and h(B=0) == b.ATTN_ERR_SHAPE and h(dq=ok + 8) == b.ATTN_ERR_ALIGN
-    assert h(D=64) == b.ATTN_ERR_UNSUPPORTED_D and h(D=256) == b.ATTN_ERR_UNSUPPORTED_D
+    assert h(D=256) == b.ATTN_ERR_UNSUPPORTED_D and h(D=96) == b.ATTN_ERR_UNSUPPORTED_D
     assert h(scale=0.0) == b.ATTN_ERR_SCALE
 
 

@@ -148,6 +148,10 @@ def run_bwd(B, q, k, v, d_o, causal, scale):
 
 
 BWD_SMALL = [
+    (1, 1, 128, 128, 64, False),
+    (2, 3, 257, 257, 64, True),
+    (1, 1, 1023, 1025, 64, False),
+    (1, 2, 700, 100, 64, True),
     (1, 1, 1, 300, 128, False),
     (2, 2, 300, 431, 128, False),
     (1, 3, 515, 515, 128, True),
@@ -192,8 +196,12 @@ def test_bwd_paper_shape_heads_in_full(B):
 
 
 def test_bwd_f16_rejects_what_it_does_not_cover(B):
-    z = torch.zeros((1, 1, 8, 64), dtype=torch.float16, device="cuda")
+    z = torch.zeros((1, 1, 8, 256), dtype=torch.float16, device="cuda")
     lse = torch.zeros((1, 1, 8), dtype=torch.float32, device="cuda")
     with pytest.raises(B.AttnError) as e:
         B.attn_bwd_f16(z, z, z, z, z, lse)
     assert e.value.status == B.ATTN_ERR_UNSUPPORTED_D
+    z = torch.zeros((1, 1, 8, 64), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.AttnError) as e:
+        B.attn_bwd_f16(z, z, z, z, z, lse, scale=0.0)
+    assert e.value.status == B.ATTN_ERR_SCALE
