@@ -114,7 +114,13 @@ int attn_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float
                      int B, int H, int S_q, int S_kv, int D, int causal, float scale,
                      void *stream);
 
-/* Bytes of workspace attn_fwd_splitkv needs: n_split * B * H * S_q * (D + 1) * 4; -1 on invalid arguments. */
+/* attn_fwd_splitkv on IEEE fp16 tensors (q, k, v, o); everything else as attn_fwd_splitkv; pairs with attn_fwd_f16. */
+int attn_fwd_splitkv_f16(const void *q, const void *k, const void *v, void *o, float *lse,
+                         void *workspace, long long workspace_bytes, int n_split,
+                         int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+                         void *stream);
+
+/* Bytes of workspace attn_fwd_splitkv (either element type) needs: n_split * B * H * S_q * (D + 1) * 4; -1 on invalid arguments. */
 long long attn_fwd_splitkv_workspace_bytes(int B, int H, int S_q, int D, int n_split);
 
 /*

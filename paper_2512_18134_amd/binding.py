@@ -24,6 +24,8 @@ _lib.attn_fwd_f16.argtypes = _lib.attn_fwd.argtypes
 _lib.attn_fwd_splitkv.restype = ctypes.c_int
 _lib.attn_fwd_splitkv.argtypes = ([ctypes.c_void_p] * 6 + [ctypes.c_longlong, ctypes.c_int] + [ctypes.c_int] * 6
                                   + [ctypes.c_float, ctypes.c_void_p])
+_lib.attn_fwd_splitkv_f16.restype = ctypes.c_int
+_lib.attn_fwd_splitkv_f16.argtypes = _lib.attn_fwd_splitkv.argtypes
 _lib.attn_fwd_splitkv_workspace_bytes.restype = ctypes.c_longlong
 _lib.attn_fwd_splitkv_workspace_bytes.argtypes = [ctypes.c_int] * 5
 _lib.attn_bwd.restype = ctypes.c_int
@@ -214,22 +216,42 @@ def attn_fwd_splitkv_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, ws_ptr, ws_bytes, 
                                      B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
 
 
+def attn_fwd_splitkv_f16_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, ws_ptr, ws_bytes, n_split,
+                             B, H, S_q, S_kv, D, causal, scale, stream_ptr):
+    """The C entry point attn_fwd_splitkv_f16 with raw integer addresses; returns the attn_status."""
+    return int(_lib.attn_fwd_splitkv_f16(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, ws_ptr, ws_bytes, n_split,
+                                         B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
+
+
 def attn_fwd_splitkv(q, k, v, n_split, o=None, lse=None, workspace=None, causal=False, scale=None, stream=None):
     """attn_fwd_splitkv on torch device tensors (bf16).  `workspace`: a contiguous GPU tensor of at least
     attn_fwd_splitkv_workspace_bytes(...) bytes (allocated when not given).  Returns (o, lse)."""
     import torch
+    return _marshal_splitkv(attn_fwd_splitkv_raw, torch.bfloat16, q, k, v, n_split, o, lse, workspace, causal, scale,
+                            stream)
+
+
+def attn_fwd_splitkv_f16(q, k, v, n_split, o=None, lse=None, workspace=None, causal=False, scale=None, stream=None):
+    """attn_fwd_splitkv_f16 on torch device tensors: as attn_fwd_splitkv, with fp16 tensors."""
+    import torch
+    return _marshal_splitkv(attn_fwd_splitkv_f16_raw, torch.float16, q, k, v, n_split, o, lse, workspace, causal, scale,
+                            stream)
+
+
+def _marshal_splitkv(entry, dt, q, k, v, n_split, o, lse, workspace, causal, scale, stream):
+    import torch
 
     for t in (q, k, v):
-        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
-            raise TypeError("q, k, v must be contiguous 4-D bf16 tensors on the GPU")
+        if t.dtype != dt or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise TypeError("q, k, v must be contiguous 4-D %s tensors on the GPU" % dt)
     B, H, S_q, D = q.shape
     if k.shape != v.shape or k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
         raise ValueError("q, k, v shapes do not agree")
     S_kv = k.shape[2]
     o = torch.empty_like(q) if o is None else o
     lse = torch.empty((B, H, S_q), dtype=torch.float32, device=q.device) if lse is None else lse
-    if o.dtype != torch.bfloat16 or o.shape != q.shape or not o.is_contiguous() or not o.is_cuda:
-        raise TypeError("o must be a contiguous bf16 GPU tensor shaped like q")
+    if o.dtype != dt or o.shape != q.shape or not o.is_contiguous() or not o.is_cuda:
+        raise TypeError("o must be a contiguous GPU tensor shaped and typed like q")
     if lse.dtype != torch.float32 or tuple(lse.shape) != (B, H, S_q) or not lse.is_contiguous() or not lse.is_cuda:
         raise TypeError("lse must be a contiguous fp32 GPU tensor [B,H,S_q]")
     need = attn_fwd_splitkv_workspace_bytes(B, H, S_q, D, n_split)
@@ -242,9 +264,9 @@ def attn_fwd_splitkv(q, k, v, n_split, o=None, lse=None, workspace=None, causal=
     if stream is None:
         stream = torch.cuda.current_stream(q.device)
     with torch.cuda.device(q.device):
-        rc = attn_fwd_splitkv_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
-                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), n_split,
-                                  B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
+        rc = entry(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                   workspace.data_ptr(), workspace.numel() * workspace.element_size(), n_split,
+                   B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
     if rc != ATTN_OK:
         raise AttnError(rc)
     return o, lse

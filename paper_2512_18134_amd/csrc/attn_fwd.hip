@@ -185,9 +185,36 @@ extern "C" long long attn_fwd_splitkv_workspace_bytes(int B, int H, int S_q, int
     return (long long)n_split * B * H * S_q * (D + 1) * 4;
 }
 
-extern "C" int attn_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *lse, void *workspace,
-                                long long workspace_bytes, int n_split, int B, int H, int S_q, int S_kv, int D,
-                                int causal, float scale, void *stream)
+template <int D, bool F16>
+static int launch_splitkv(Params &p, int BH, int n_eff, void *o, float *lse, hipStream_t st)
+{
+    typedef typename std::conditional<F16, _Float16, attn::bf16_t>::type out_t;
+    const long long n_rows = (long long)BH * p.S_q;
+    constexpr int BM = 256;
+    p.n_qt = (p.S_q + BM - 1) / BM;
+    const long long total = (long long)BH * p.n_qt * n_eff;
+    if (total > 0x7fffffffLL)
+        return ATTN_ERR_SHAPE;
+    p.total_wg = (int)total;
+    const int lds = 8 * 64 * D * 2;
+    auto kern = attn::attn_fwd_asm_kernel<D, false, F16, true>;
+    if (!allow_lds(kern, lds))
+        return ATTN_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(512), lds, st, p);
+    if (hipGetLastError() != hipSuccess)
+        return ATTN_ERR_LAUNCH;
+    const int rpb = 256 / (D / 4);
+    const long long blocks = (n_rows + rpb - 1) / rpb;
+    const unsigned grid = (unsigned)(blocks < 8192 ? blocks : 8192);
+    hipLaunchKernelGGL((attn::attn_splitkv_merge_kernel<D, out_t>), dim3(grid), dim3(256), 0, st, p.o_part, p.lse_part,
+                       static_cast<out_t *>(o), lse, n_rows, n_eff);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+template <bool F16>
+static int splitkv_entry(const void *q, const void *k, const void *v, void *o, float *lse, void *workspace,
+                         long long workspace_bytes, int n_split, int B, int H, int S_q, int S_kv, int D, int causal,
+                         float scale, void *stream)
 {
     Params p;
     const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
@@ -209,35 +236,33 @@ extern "C" int attn_fwd_splitkv(const void *q, const void *k, const void *v, voi
         return ATTN_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int n_eff = split_plan(S_kv, n_split, p.split_len);
-    if (n_eff == 1)  // one range: the plain kernel writes o and lse itself
+    if (n_eff == 1) {  // one range: the plain kernel writes o and lse itself
+        if (F16)
+            return D == 64 ? launch_asm_f16<64>(p, B * H, 0, st) : launch_asm_f16<128>(p, B * H, 0, st);
         return D == 64 ? launch_asm<64>(p, B * H, 0, st) : launch_asm<128>(p, B * H, 0, st);
+    }
     const long long n_rows = (long long)B * H * S_q;
     p.n_split = n_eff;
     p.o_part = static_cast<float *>(workspace);
     p.lse_part = p.o_part + (long long)n_eff * n_rows * D;
-    constexpr int BM = 256;
-    p.n_qt = (S_q + BM - 1) / BM;
-    const long long total = (long long)B * H * p.n_qt * n_eff;
-    if (total > 0x7fffffffLL)
-        return ATTN_ERR_SHAPE;
-    p.total_wg = (int)total;
-    const int lds = 8 * 64 * D * 2;
-    auto kern = D == 64 ? attn::attn_fwd_asm_kernel<64, false, false, true> : attn::attn_fwd_asm_kernel<128, false, false, true>;
-    if (!allow_lds(kern, lds))
-        return ATTN_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(512), lds, st, p);
-    if (hipGetLastError() != hipSuccess)
-        return ATTN_ERR_LAUNCH;
-    const int rpb = 256 / (D / 4);
-    const long long blocks = (n_rows + rpb - 1) / rpb;
-    const unsigned grid = (unsigned)(blocks < 8192 ? blocks : 8192);
-    if (D == 64)
-        hipLaunchKernelGGL(attn::attn_splitkv_merge_kernel<64>, dim3(grid), dim3(256), 0, st, p.o_part, p.lse_part,
-                           static_cast<attn::bf16_t *>(o), lse, n_rows, n_eff);
-    else
-        hipLaunchKernelGGL(attn::attn_splitkv_merge_kernel<128>, dim3(grid), dim3(256), 0, st, p.o_part, p.lse_part,
-                           static_cast<attn::bf16_t *>(o), lse, n_rows, n_eff);
-    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+    return D == 64 ? launch_splitkv<64, F16>(p, B * H, n_eff, o, lse, st)
+                   : launch_splitkv<128, F16>(p, B * H, n_eff, o, lse, st);
+}
+
+extern "C" int attn_fwd_splitkv(const void *q, const void *k, const void *v, void *o, float *lse, void *workspace,
+                                long long workspace_bytes, int n_split, int B, int H, int S_q, int S_kv, int D,
+                                int causal, float scale, void *stream)
+{
+    return splitkv_entry<false>(q, k, v, o, lse, workspace, workspace_bytes, n_split, B, H, S_q, S_kv, D, causal,
+                                scale, stream);
+}
+
+extern "C" int attn_fwd_splitkv_f16(const void *q, const void *k, const void *v, void *o, float *lse, void *workspace,
+                                    long long workspace_bytes, int n_split, int B, int H, int S_q, int S_kv, int D,
+                                    int causal, float scale, void *stream)
+{
+    return splitkv_entry<true>(q, k, v, o, lse, workspace, workspace_bytes, n_split, B, H, S_q, S_kv, D, causal,
+                               scale, stream);
 }
 
 extern "C" int attn_fwd_f16(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,

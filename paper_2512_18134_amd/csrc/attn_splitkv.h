@@ -10,10 +10,11 @@
 namespace attn {
 
 // One row = D/4 threads, 4 head-dimension elements each.  HBM-bound: reads n_split * (D + 1) floats per row.
-template <int D>
+// OUT: bf16_t or _Float16, the element type of o.
+template <int D, typename OUT>
 __global__ __launch_bounds__(256) void attn_splitkv_merge_kernel(const float *__restrict__ o_part,
                                                                  const float *__restrict__ lse_part,
-                                                                 bf16_t *__restrict__ o, float *__restrict__ lse,
+                                                                 OUT *__restrict__ o, float *__restrict__ lse,
                                                                  long long n_rows, int n_split)
 {
     constexpr int TPR = D / 4;
@@ -37,9 +38,11 @@ __global__ __launch_bounds__(256) void attn_splitkv_merge_kernel(const float *__
         const float total = m + logf(sum);
         acc *= 1.f / sum;
         const f32x2 lo = {acc[0], acc[1]}, hi = {acc[2], acc[3]};
-        const bf16x2 blo = __builtin_convertvector(lo, bf16x2), bhi = __builtin_convertvector(hi, bf16x2);
-        const bf16x4 out = {blo[0], blo[1], bhi[0], bhi[1]};
-        *reinterpret_cast<bf16x4 *>(o + r * D + 4 * sub) = out;
+        typedef OUT out2 __attribute__((ext_vector_type(2)));
+        typedef OUT out4 __attribute__((ext_vector_type(4)));
+        const out2 blo = __builtin_convertvector(lo, out2), bhi = __builtin_convertvector(hi, out2);  // RNE
+        const out4 out = {blo[0], blo[1], bhi[0], bhi[1]};
+        *reinterpret_cast<out4 *>(o + r * D + 4 * sub) = out;
         if (sub == 0)
             lse[r] = total;
     }

@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_header_symbols_are_exported(binding):
     names = declared_symbols()
-    assert {"attn_fwd", "attn_fwd_f16", "attn_fwd_splitkv", "attn_bwd", "attn_bwd_f16", "attn_strerror",
+    assert {"attn_fwd", "attn_fwd_f16", "attn_fwd_splitkv", "attn_fwd_splitkv_f16", "attn_bwd", "attn_bwd_f16", "attn_strerror",
             "attn_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
@@ -82,7 +82,8 @@ def test_f16_entry_validates_like_the_bf16_one_and_narrows_d_and_scale(binding):
     assert f(S_kv=1 << 24, D=128) == b.ATTN_ERR_SHAPE  # one head of K beyond 32-bit byte offsets
 
 
-def test_splitkv_entry_validates_before_any_launch(binding):
+@pytest.mark.parametrize("entry", ["attn_fwd_splitkv_raw", "attn_fwd_splitkv_f16_raw"])
+def test_splitkv_entry_validates_before_any_launch(binding, entry):
     b = binding
     ok = 0x1000
     names = ("q", "k", "v", "o", "lse", "ws")
@@ -91,7 +92,7 @@ def test_splitkv_entry_validates_before_any_launch(binding):
         ws_bytes = kw.get("ws_bytes", 1 << 40)
         rest = [kw.get(n, d) for n, d in (("n_split", 4), ("B", 1), ("H", 1), ("S_q", 8), ("S_kv", 8), ("D", 64),
                                            ("causal", 0), ("scale", 0.125), ("stream", 0))]
-        return b.attn_fwd_splitkv_raw(*(ptrs + [ws_bytes] + rest))
+        return getattr(b, entry)(*(ptrs + [ws_bytes] + rest))
     for n in names:
         assert f(**{n: 0}) == b.ATTN_ERR_NULL
     for n in ("B", "H", "S_q", "S_kv"):

@@ -71,6 +71,28 @@ def test_split_matches_oracle(B, case):
     assert eo <= O_TOL and el <= LSE_TOL
 
 
+@pytest.mark.parametrize("case", [(1, 2, 100, 1000, 128, 3), (2, 1, 300, 4097, 64, 4), (1, 3, 1, 777, 128, 5),
+                                  (1, 1, 64, 64, 128, 2), (1, 1, 40, 16384, 64, 256)],
+                         ids=lambda c: "f16_B%d_H%d_Sq%d_Skv%d_D%d_split%d" % c)
+def test_split_f16_matches_oracle(B, case):
+    # attn_fwd_splitkv_f16: same launch, fp16 tensors; the O bar of the fp16 forward tests (4e-3)
+    b, h, sq, skv, d, n_split = case
+    print("splitkv f16 case", case, flush=True)
+    q, k, v = synth.make_qkv(b, h, sq, skv, d, seed=800 + skv + n_split, dtype="f16")
+    scale = synth.default_scale(d)
+    dev = lambda bits: torch.from_numpy(bits.view(np.int16)).cuda().view(torch.float16)
+    o = torch.full((b, h, sq, d), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((b, h, sq), float("nan"), dtype=torch.float32, device="cuda")
+    B.attn_fwd_splitkv_f16(dev(q), dev(k), dev(v), n_split, o, lse, scale=scale)
+    torch.cuda.synchronize()
+    og, lg = o.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    orf, lrf = attn_ref(q, k, v, False, scale, dtype="f16")
+    assert np.all(np.isfinite(og)) and np.all(np.isfinite(lg))
+    eo, el = np.max(np.abs(og - orf)), np.max(np.abs(lg - lrf))
+    print("%s max|dO|=%.3e max|dLSE|=%.3e" % (case, eo, el), flush=True)
+    assert eo <= 4e-3 and el <= LSE_TOL
+
+
 def test_sharp_softmax_and_agreement_with_unsplit(B):
     # per-row offsets: the ranges have very different maxima, so the merge weights span many decades
     b, h, sq, skv, d = 1, 4, 200, 3000, 128
