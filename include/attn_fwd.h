@@ -77,7 +77,6 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * Arguments, layout, ownership and error behaviour are those of attn_fwd, except:
  *   q, k, v, o   hold IEEE binary16 instead of bf16; both contractions run on fp16
  *                MFMA with fp32 accumulation and P is rounded to fp16 (nearest even)
- *   D            64 or 128 (256 returns ATTN_ERR_UNSUPPORTED_D)
  *   scale        finite and > 0 (0 returns ATTN_ERR_SCALE)
  *   S_kv * D     below 2^30 (one head of K addressed with 32-bit byte offsets;
  *                larger returns ATTN_ERR_SHAPE)

@@ -32,9 +32,9 @@ def generate_sources(verbose=False):
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
     gen2 = os.path.join(HERE, "csrc", "gen_attn_loop2.py")
-    for name in ("d128a", "d256a"):
-        out = os.path.join(out_dir, "attn_loop_%s.inc" % name)
-        cmd = [sys.executable, gen2, name, out]
+    for name, dtype in (("d128a", "bf16"), ("d256a", "bf16"), ("d256a", "f16")):
+        out = os.path.join(out_dir, "attn_loop_%s%s.inc" % (name, "" if dtype == "bf16" else "_" + dtype))
+        cmd = [sys.executable, gen2, name, out, dtype]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

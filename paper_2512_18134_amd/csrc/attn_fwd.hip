@@ -99,13 +99,13 @@ int launch_asm_f16(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_asm_kernel<D, false, true>, p, BH, 256, 512, LDS, stream);
 }
 
-template <int D, int QB>
+template <int D, int QB, bool F16 = false>
 int launch_asm2(const Params &p, int BH, int causal, hipStream_t stream)
 {
     constexpr int LDS = 8 * 32 * D * 2;
     if (causal)
-        return launch(attn::attn_fwd_asm2_kernel<D, QB, true>, p, BH, 128 * QB, 256, LDS, stream);
-    return launch(attn::attn_fwd_asm2_kernel<D, QB, false>, p, BH, 128 * QB, 256, LDS, stream);
+        return launch(attn::attn_fwd_asm2_kernel<D, QB, true, F16>, p, BH, 128 * QB, 256, LDS, stream);
+    return launch(attn::attn_fwd_asm2_kernel<D, QB, false, F16>, p, BH, 128 * QB, 256, LDS, stream);
 }
 
 // Debug only: ATTN_FWD_VARIANT picks a tiling / schedule variant of the pipelined kernel.
@@ -272,14 +272,14 @@ extern "C" int attn_fwd_f16(const void *q, const void *k, const void *v, void *o
     const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
     if (rc != ATTN_OK)
         return rc;
-    // fp16 runs on the hand-scheduled 8-wave kernel only
-    if (D == 256)
-        return ATTN_ERR_UNSUPPORTED_D;
+    // fp16 runs on the hand-scheduled kernels only
     if ((long long)S_kv * D * 2 >= (1LL << 31))
         return ATTN_ERR_SHAPE;
     if (!(scale > 0.f))
         return ATTN_ERR_SCALE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (D == 256)
+        return launch_asm2<256, 1, true>(p, B * H, causal, st);
     return D == 64 ? launch_asm_f16<64>(p, B * H, causal, st) : launch_asm_f16<128>(p, B * H, causal, st);
 }
 

@@ -27,10 +27,15 @@ struct F32Vec<1> {
     static __device__ __forceinline__ float get(const type &v, int) { return v; }
 };
 
-template <int D, int QB, bool CAUSAL>
+template <int D, int QB, bool CAUSAL, bool F16 = false>
 __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
 {
-    static_assert((D == 128 && QB == 2) || (D == 256 && QB == 1), "supported tilings");
+    static_assert((D == 128 && QB == 2 && !F16) || (D == 256 && QB == 1), "supported tilings");
+    typedef typename std::conditional<F16, ElemF16, ElemBF16>::type E;
+    typedef typename E::t elem_t;
+    typedef typename E::x2 ex2;
+    typedef typename E::x4 ex4;
+    typedef typename E::x8 ex8;
     constexpr int BN = 32, NW = 4, BM = NW * 32 * QB, NST = 4;
     constexpr int CPR = D / 8;
     constexpr int KS = D / 16;
@@ -55,9 +60,9 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
     const int q0 = qt * BM;
     auto qcol = [&](int qb) { return q0 + (wave * QB + qb) * 32 + lq; };
 
-    const bf16_t *qg = p.q + (size_t)bh * p.S_q * D;
-    const bf16_t *k_head = p.k + (size_t)bh * p.S_kv * D;
-    const bf16_t *v_head = p.v + (size_t)bh * p.S_kv * D;
+    const elem_t *qg = reinterpret_cast<const elem_t *>(p.q) + (size_t)bh * p.S_q * D;
+    const elem_t *k_head = reinterpret_cast<const elem_t *>(p.k) + (size_t)bh * p.S_kv * D;
+    const elem_t *v_head = reinterpret_cast<const elem_t *>(p.v) + (size_t)bh * p.S_kv * D;
 
     int kv_end = p.S_kv;
     if (CAUSAL)
@@ -81,7 +86,7 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
         U32Vec<NLD>::set(dma_choff_v, i, dma_choff[i]);
         U32Vec<NLD>::set(dma_voff_v, i, dma_row[i] * ROWB + dma_choff[i]);
     }
-    auto issue_tile = [&](const bf16_t *base, uint32_t ring_off, int stage, int t) {
+    auto issue_tile = [&](const elem_t *base, uint32_t ring_off, int stage, int t) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int r = min(t * BN + (int)dma_row[i], p.S_kv - 1);
@@ -126,13 +131,13 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
     issue_tile(v_head, VRING, 0, 0);
     issue_tile(v_head, VRING, 1, 1);
 
-    bf16x8 bq[QB][KS];
+    ex8 bq[QB][KS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const bf16_t *src = qg + (size_t)min(qcol(qb), p.S_q - 1) * D + 8 * g;
+        const elem_t *src = qg + (size_t)min(qcol(qb), p.S_q - 1) * D + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            bq[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+            bq[qb][ks] = *reinterpret_cast<const ex8 *>(src + 16 * ks);
     }
     f32x16 o_acc[QB * DB];
 #pragma unroll
@@ -153,10 +158,10 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
             s_init[qb][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = *(ATTN_LDS_PTR(const bf16x8))(uintptr_t)(koff[ks]);
+        const ex8 a = *(ATTN_LDS_PTR(const ex8))(uintptr_t)(koff[ks]);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-            s_init[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[qb][ks], s_init[qb], 0, 0, 0);
+            s_init[qb] = E::mfma(a, bq[qb][ks], s_init[qb]);
     }
 
     typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
 #pragma unroll
     for (int i = 0; i < NQP; ++i) {
         struct Four {
-            bf16x8 a[4];
+            ex8 a[4];
         } f;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
@@ -180,8 +185,10 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
 
     if constexpr (D == 128) {
 #include "generated/attn_loop_d128a.inc"
-    } else {
+    } else if constexpr (!F16) {
 #include "generated/attn_loop_d256a.inc"
+    } else {
+#include "generated/attn_loop_d256a_f16.inc"
     }
 
     // ---- epilogue
@@ -192,7 +199,7 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
         const float inv = 1.f / l_tot;
         const int qrow = qcol(qb);
         if (qrow < p.S_q) {
-            bf16_t *orow = p.o + ((size_t)bh * p.S_q + qrow) * D;
+            elem_t *orow = reinterpret_cast<elem_t *>(p.o) + ((size_t)bh * p.S_q + qrow) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -200,10 +207,10 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
                     const f32x16 &oa = o_acc[qb * DB + db];
                     const f32x2 lo = {oa[4 * rb + 0] * inv, oa[4 * rb + 1] * inv};
                     const f32x2 hi = {oa[4 * rb + 2] * inv, oa[4 * rb + 3] * inv};
-                    const bf16x2 blo = __builtin_convertvector(lo, bf16x2);
-                    const bf16x2 bhi = __builtin_convertvector(hi, bf16x2);
-                    const bf16x4 out = {blo[0], blo[1], bhi[0], bhi[1]};
-                    *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * rb + 4 * g) = out;
+                    const ex2 blo = __builtin_convertvector(lo, ex2);  // round to nearest even
+                    const ex2 bhi = __builtin_convertvector(hi, ex2);
+                    const ex4 out = {blo[0], blo[1], bhi[0], bhi[1]};
+                    *reinterpret_cast<ex4 *>(orow + 32 * db + 8 * rb + 4 * g) = out;
                 }
             if (g == 0)
                 p.lse[(size_t)bh * p.S_q + qrow] =

@@ -30,9 +30,11 @@ CONFIGS = {
 
 
 class Gen:
-    def __init__(self, name, NF=4, PFD=3):
+    def __init__(self, name, NF=4, PFD=3, dtype="bf16"):
         cfg = CONFIGS[name]
         self.name = name
+        assert dtype in ("bf16", "f16")
+        self.dtype = dtype                       # element type of Q, K, V and of the rounded P
         self.D, self.QB, self.NACC = cfg["D"], cfg["QB"], cfg["NACC"]
         D, QB, NACC = self.D, self.QB, self.NACC
         self.NW = 4
@@ -146,12 +148,12 @@ class Gen:
         if kind == "pv":
             kc, db = a, b
             o = self.ar(self.O + 16 * (qb * self.DB + db), 16)
-            return "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (o, f, self.vr(P_prev + qb * 8 + kc * 4, 4), o)
+            return "v_mfma_f32_32x32x16_%s %s, %s, %s, %s" % (self.dtype, o, f, self.vr(P_prev + qb * 8 + kc * 4, 4), o)
         ks = a
         acc = ks % self.NACC
         s = self.vr(self.s_reg(S_nxt, qb, acc), 16)
         q = self.ar(self.Q + 4 * (qb * self.KS + ks), 4)
-        return "v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (s, f, q, "0" if ks < self.NACC else s)
+        return "v_mfma_f32_32x32x16_%s %s, %s, %s, %s" % (self.dtype, s, f, q, "0" if ks < self.NACC else s)
 
     # ---------------------------------------------------------- softmax programs
     def max_ops(self, S_cur):
@@ -215,7 +217,7 @@ class Gen:
             qb, k = p
             return ["v_add_f32 v%d, v%d, v%d" % (self.LA + qb, self.LA + qb, e0),
                     "v_add_f32 v%d, v%d, v%d" % (self.LB + qb, self.LB + qb, e1),
-                    "v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (P_new + qb * 8 + k, e0, e1)]
+                    "v_cvt_pk_%s_f32 v%d, v%d, v%d" % (self.dtype, P_new + qb * 8 + k, e0, e1)]
         ops = []
         n = len(pairs)
         for t in range(n + 2):
@@ -508,6 +510,6 @@ class Gen:
 
 
 if __name__ == "__main__":
-    text = Gen(sys.argv[1]).emit_inc()
+    text = Gen(sys.argv[1], dtype=sys.argv[3] if len(sys.argv) > 3 else "bf16").emit_inc()
     with open(sys.argv[2], "w") as f:
         f.write(text)

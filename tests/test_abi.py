@@ -64,7 +64,7 @@ def test_validation_happens_before_any_launch(binding):
         assert f(scale=s) == b.ATTN_ERR_SCALE
 
 
-def test_f16_entry_validates_like_the_bf16_one_and_narrows_d_and_scale(binding):
+def test_f16_entry_validates_like_the_bf16_one_and_narrows_scale_and_size(binding):
     b = binding
     ok = 0x1000
     f = lambda **kw: b.attn_fwd_f16_raw(*[kw.get(n, d) for n, d in (
@@ -74,7 +74,7 @@ def test_f16_entry_validates_like_the_bf16_one_and_narrows_d_and_scale(binding):
         assert f(**{name: 0}) == b.ATTN_ERR_NULL
     for name in ("B", "H", "S_q", "S_kv"):
         assert f(**{name: 0}) == b.ATTN_ERR_SHAPE
-    for D in (0, 32, 96, 256, 512):
+    for D in (0, 32, 96, 512):
         assert f(D=D) == b.ATTN_ERR_UNSUPPORTED_D
     assert f(q=ok + 8) == b.ATTN_ERR_ALIGN
     for s in (float("nan"), float("inf"), -1.0, 0.0):

@@ -50,6 +50,10 @@ SMALL = [
     (1, 2, 100, 700, 128, True),
     (1, 1, 1023, 1025, 64, False),
     (3, 5, 64, 64, 128, True),
+    (1, 2, 300, 431, 256, False),
+    (2, 2, 515, 515, 256, True),
+    (1, 1, 1, 300, 256, False),
+    (1, 3, 129, 1000, 256, True),
 ]
 
 
@@ -67,7 +71,7 @@ def test_small_shapes_elementwise(B, shape):
     assert eo <= O_TOL and el <= LSE_TOL
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 def test_sharp_softmax(B, d):
     # per-row offsets on Q and K: a few keys dominate every row and the running maximum moves often
     b, h, s = 1, 2, 777
@@ -118,7 +122,7 @@ def test_paper_shape_sampled_rows(B):
 
 
 def test_f16_rejects_what_it_does_not_cover(B):
-    q = torch.zeros((1, 1, 8, 256), dtype=torch.float16, device="cuda")
+    q = torch.zeros((1, 1, 8, 96), dtype=torch.float16, device="cuda")
     with pytest.raises(B.AttnError) as e:
         B.attn_fwd_f16(q, q, q)
     assert e.value.status == B.ATTN_ERR_UNSUPPORTED_D
