@@ -19,7 +19,9 @@ gfx950 costs, and reproduces the paper's running example.
 
 The search is exhaustive (smallest I first, then smallest L): graphs here have a
 handful of tile-level instructions, which is the granularity the paper
-schedules at.  Costs are normalised first (Section 5.2): integers C' with
+schedules at.  Section 4.2's memory-capacity constraint and Section 4.3's
+warp-assignment constraints (`Warps`, `joint_schedule`) extend it to the joint
+problem the paper solves.  Costs are normalised first (Section 5.2): integers C' with
 sum <= U whose pairwise ratios stay as close as possible to those of C.
 """
 import itertools
@@ -227,6 +229,173 @@ def fits(loop, M, I, footprint, capacity, resident=0):
     return max(live_footprint(loop, M, I, footprint, resident)) <= capacity
 
 
+# ------------------------------------------------------------------ warp assignment (Section 4.3)
+class Warps:
+    """The inputs of the paper's warp-assignment constraints, for one loop:
+
+      n_warps           warps (wavefronts here) the instructions may be spread over
+      variable_latency  instructions whose latency is not known statically; they all go to the designated
+                        warp W_vl (index 0), and nothing else does.  With none, every warp is an ordinary one.
+      regs, reg_limit   registers a result occupies while live (Section 4.2's liveness), and the budget of
+                        one warp; a result lives in the registers of the warp that produced it
+      spillcost         cycles to hand a result to another warp through shared memory (LDS): added to the
+                        delay of every edge whose ends sit on different warps
+      blocking          edges (u, v) whose consumer must block on synchronisation before it can read the
+                        result; an edge that crosses warps is blocking as well (the transfer needs a wait)
+    """
+
+    def __init__(self, n_warps, reg_limit=None, regs=None, variable_latency=(), spillcost=None, blocking=()):
+        self.n_warps = n_warps
+        self.reg_limit = reg_limit
+        self.regs = dict(regs or {})
+        self.variable_latency = frozenset(variable_latency)
+        self.spillcost = dict(spillcost or {})
+        self.blocking = frozenset(blocking)
+        self.w_vl = 0 if self.variable_latency else None
+
+
+def warp_edges(loop, A, ws):
+    """The loop's edges with the cross-warp transfer cost added (Cross-Warp Spills)."""
+    return [(u, v, d + (ws.spillcost.get(u, 0) if A[u] != A[v] else 0), delta) for u, v, d, delta in loop.edges]
+
+
+def is_valid_assignment(loop, M, I, A, ws):
+    """(M, I) with the warp assignment A (instruction -> warp index) against the constraints of Sections
+    4.1-4.3: dependences with cross-warp delays, modular resource use, warp uniqueness, the variable-latency
+    warp, the register limit of every warp and the concurrency constraint."""
+    if set(A) != set(loop.rrt) or any(not (0 <= w < ws.n_warps) for w in A.values()):
+        return False
+    for v in loop.rrt:
+        if (v in ws.variable_latency) != (ws.w_vl is not None and A[v] == ws.w_vl):
+            return False
+    for u, v, d, delta in warp_edges(loop, A, ws):
+        if M[v] + I * delta < M[u] + d:
+            return False
+    for row in modular_rrt(loop, M, I):
+        for unit, n in row.items():
+            if n > loop.capacity[unit]:
+                return False
+    if ws.reg_limit is not None:
+        for w in range(ws.n_warps):
+            mine = {v: ws.regs.get(v, 0) for v in loop.rrt if A[v] == w}
+            if max(live_footprint(loop, M, I, mine)) > ws.reg_limit:
+                return False
+    # concurrency: when v issues behind a blocking edge, its warp has nothing else in flight
+    for u, v, _, _ in loop.edges:
+        if (u, v) in ws.blocking or A[u] != A[v]:
+            for o in loop.rrt:
+                if o != v and A[o] == A[v]:
+                    if (M[v] - M[o]) % I < duration(loop, o) or duration(loop, o) >= I:
+                        return False
+    return True
+
+
+def _assignments(loop, ws):
+    """Warp assignments up to renaming of the ordinary warps (they are interchangeable)."""
+    names = [v for v in loop.order if v not in ws.variable_latency]
+    first = 0 if ws.w_vl is None else 1
+    def rec(i, used, cur):
+        if i == len(names):
+            A = dict(cur)
+            for v in ws.variable_latency:
+                A[v] = ws.w_vl
+            yield A
+            return
+        for w in range(first, min(used + 1, ws.n_warps - 1) + 1):
+            cur[names[i]] = w
+            yield from rec(i + 1, max(used, w + 1), cur)
+        cur.pop(names[i], None)
+    yield from rec(0, first, {})
+
+
+def _search(loop, I, L, edges, accept, A=None, blocked=()):
+    """Depth-first search for start times with schedule length exactly L.  Every instruction is placed no
+    earlier than its already placed predecessors allow; a partial schedule is dropped as soon as it breaks
+    a dependence, oversubscribes a unit in some cycle mod I, or (with a warp assignment A and the set
+    `blocked` of instructions that issue behind a blocking wait) breaks the concurrency constraint;
+    `accept(M)` decides a complete schedule."""
+    names = loop.order
+    dur = {v: duration(loop, v) for v in names}
+    M = {}
+    table = [dict() for _ in range(I)]
+
+    def occupy(v, t, sign):
+        ok = True
+        for c, use in enumerate(loop.rrt[v]):
+            row = table[(t + c) % I]
+            for unit, n in use.items():
+                row[unit] = row.get(unit, 0) + sign * n
+                if row[unit] > loop.capacity[unit]:
+                    ok = False
+        return ok
+
+    def concurrent_ok(v, t):
+        if A is None:
+            return True
+        for o, to in M.items():
+            if o == v or A[o] != A[v]:
+                continue
+            if v in blocked and ((t - to) % I < dur[o] or dur[o] >= I):
+                return False
+            if o in blocked and ((to - t) % I < dur[v] or dur[v] >= I):
+                return False
+        return True
+
+    def rec(i):
+        if i == len(names):
+            return dict(M) if length(loop, M) == L and accept(M) else None
+        v = names[i]
+        lo = 0
+        for a, b, d, delta in edges:
+            if b == v and a in M and a != v:
+                lo = max(lo, M[a] + d - I * delta)
+            if a == v and b == v and I * delta < d:
+                return None                      # a recurrence on v itself that I cannot satisfy
+        for t in range(lo, L - dur[v] + 1):
+            ok = True
+            for a, b, d, delta in edges:
+                if a == v and b in M and b != v and M[b] + I * delta < t + d:
+                    ok = False
+                    break
+            if not ok or not concurrent_ok(v, t):
+                continue
+            M[v] = t
+            if occupy(v, t, +1):
+                got = rec(i + 1)
+                if got is not None:
+                    return got
+            occupy(v, t, -1)
+            del M[v]
+        return None
+    return rec(0)
+
+
+def joint_schedule(loop, ws, max_len=None, max_interval=None):
+    """The joint problem of Section 4: the smallest I, then the smallest L, over modulo schedules AND warp
+    assignments; among equals the assignment that uses the fewest warps.  Returns (M, I, L, A), or None when
+    nothing fits up to max_interval (the paper's Section 5.1 then relaxes the problem)."""
+    total = sum(duration(loop, v) for v in loop.rrt)
+    max_len = max_len or 2 * total + sum(ws.spillcost.values())
+    max_interval = max_interval or max_len
+    cands = sorted(_assignments(loop, ws), key=lambda A: len(set(A.values())))
+    I = max(res_mii(loop), rec_mii(loop))
+    while I <= max_interval:
+        best = None
+        for A in cands:
+            edges = warp_edges(loop, A, ws)
+            top = max_len if best is None else best[2] - 1
+            for L in range(1, top + 1):
+                blocked = {v for u, v, _, _ in loop.edges if (u, v) in ws.blocking or A[u] != A[v]}
+                M = _search(loop, I, L, edges, lambda M: is_valid_assignment(loop, M, I, A, ws), A, blocked)
+                if M is not None:
+                    best = (M, I, L, A)
+                    break
+        if best is not None:
+            return best
+        I += 1
+    return None
+
+
 # ------------------------------------------------------------------ the paper's running example
 def paper_toy():
     """Fig. 1: S = gemm(Q,K) on the tensor core, P = exp(S) on the exp unit, O += gemm(P,V) on the
@@ -312,6 +481,12 @@ if __name__ == "__main__":
     print("  in-order interval=%d  => pipelining gain %.2fx" % (in_order_interval(g), in_order_interval(g) / I))
     print("  registers live in the steady state: max %d of 256 (two waves per SIMD)" %
           max(live_footprint(g, M, I, GFX950_D128_REGS, GFX950_D128_RESIDENT)))
+    g12, c12, _ = gfx950_attention(U=12)
+    spill = {"QK": c12["LDS_K"] + c12["LDS_V"], "SM": c12["LDS_K"] + c12["LDS_V"], "LDS_K": 1, "LDS_V": 1}
+    for limit in (256 - GFX950_D128_RESIDENT, 100, 68):
+        Mj, Ij, Lj, Aj = joint_schedule(g12, Warps(2, regs=GFX950_D128_REGS, reg_limit=limit, spillcost=spill),
+                                        max_len=17, max_interval=9)
+        print("  joint problem, %3d free registers per wave: I=%d L=%d warps=%s" % (limit, Ij, Lj, Aj))
     g, c, F = gfx950_backward_key_owner()
     M, I, L = schedule(g, max_len=4 * sum(c.values()))
     print("gfx950 backward key-owner wave: I=%d L=%d stages=%d, registers max %d (one wave per SIMD: 512)" %

@@ -121,3 +121,208 @@ def test_register_demand_matches_what_the_generators_allocate():
     assert 256 < peak_b <= 512
     genb = _load_generator("gen_attn_bwd_loop").Gen(True, 128)
     assert abs((genb.NV + genb.NA) - (2 * 32 + 2 * 16 + 128 + ms.GFX950_BWD_RESIDENT)) <= 8
+
+
+# ------------------------------------------------------------------ warp assignment (Section 4.3)
+def _unrolled_ok(loop, M, I, A, ws):
+    """The constraints of Sections 4.1-4.3 checked the way the paper writes them: on the unrolled
+    schedule, instance (v, i) issuing at cycle M[v] + i*I.  Enough iterations are unrolled that one full
+    interval [T0, T0 + I) sees every instance that can overlap it; capacity, registers and concurrency
+    are checked there, dependences on every pair of instances.  Written independently of
+    ms.is_valid_assignment (no modular arithmetic, no closed-form liveness)."""
+    cyc = lambda v: max(1, len(loop.rrt[v]))
+    max_delta = max([dl for _, _, _, dl in loop.edges] + [0])
+    T0 = max(M.values()) + max(cyc(v) for v in M) + I * max_delta
+    n_iter = (T0 + 2 * I) // I + 2 + max_delta
+    start = {(v, i): M[v] + i * I for v in M for i in range(n_iter)}
+    window = range(T0, T0 + I)
+    # warp uniqueness / variable latency
+    for v in M:
+        if not (0 <= A[v] < ws.n_warps):
+            return False
+        if ws.variable_latency and ((v in ws.variable_latency) != (A[v] == 0)):
+            return False
+    # dependences, with the cross-warp transfer excluded cycle by cycle
+    for u, v, d, delta in loop.edges:
+        for i in range(n_iter - delta):
+            t = start[(u, i)]
+            if start[(v, i + delta)] < t + d:
+                return False
+            if A[u] != A[v]:
+                for s_ in range(ws.spillcost.get(u, 0)):
+                    if start[(v, i + delta)] == t + d + s_:
+                        return False
+    # functional-unit capacity, cycle by cycle
+    for t in window:
+        use = {}
+        for (v, i), s0 in start.items():
+            if s0 <= t < s0 + len(loop.rrt[v]):
+                for unit, n in loop.rrt[v][t - s0].items():
+                    use[unit] = use.get(unit, 0) + n
+        if any(n > loop.capacity[unit] for unit, n in use.items()):
+            return False
+    # register limit per warp: a value is live from its issue until its last consumer has finished
+    # (an accumulator updated in place hands over to its next instance when that one issues)
+    if ws.reg_limit is not None:
+        for w in range(ws.n_warps):
+            for t in window:
+                live = 0
+                for (v, i), s0 in start.items():
+                    if A[v] != w:
+                        continue
+                    end = s0 + cyc(v)
+                    for a, b, d, delta in loop.edges:
+                        if a == v:
+                            sb = M[b] + (i + delta) * I
+                            end = max(end, sb + (0 if b == v else cyc(b)))
+                    if s0 <= t < end:
+                        live += ws.regs.get(v, 0)
+                if live > ws.reg_limit:
+                    return False
+    # concurrency: behind a blocking (or cross-warp) edge the consumer issues with its warp otherwise idle
+    for u, v, _, _ in loop.edges:
+        if (u, v) in ws.blocking or A[u] != A[v]:
+            for (v2, i), t in start.items():
+                if v2 != v or t not in window:
+                    continue
+                for (o, i2), s0 in start.items():
+                    if o != v and A[o] == A[v] and t - (cyc(o) - 1) <= s0 <= t:
+                        return False
+    return True
+
+
+def _brute_force_joint(loop, ws, max_len, max_interval):
+    import itertools
+    names = loop.order
+    for I in range(1, max_interval + 1):
+        best = None
+        for starts in itertools.product(range(max_len), repeat=len(names)):
+            M = dict(zip(names, starts))
+            L = ms.length(loop, M)
+            if L > max_len or (best is not None and L >= best):
+                continue
+            for warps in itertools.product(range(ws.n_warps), repeat=len(names)):
+                if _unrolled_ok(loop, M, I, dict(zip(names, warps)), ws):
+                    best = L
+                    break
+        if best is not None:
+            return I, best
+    return None
+
+
+def _blocking_example():
+    # Section 3.2's figure: an addition consumes a GEMM behind a blocking wait while an independent EXP
+    # runs; all three on different functional units
+    g = ms.Loop({"TC": 1, "EXP": 1, "ALU": 1})
+    g.op("GEMM", "TC", 2)
+    g.op("EXP", "EXP", 2)
+    g.op("ADD", "ALU", 1)
+    g.dep("GEMM", "ADD")
+    return g
+
+
+def test_blocking_synchronisation_pushes_work_to_another_warp_or_another_time():
+    g = _blocking_example()
+    blocking = [("GEMM", "ADD")]
+    # no blocking edge: one warp sustains the tensor core's interval
+    M, I, L, A = ms.joint_schedule(g, ms.Warps(1))
+    assert I == 2 and len(set(A.values())) == 1
+    # blocking wait, one warp: ADD may only issue while GEMM and EXP are not in flight -> another time,
+    # and the interval grows
+    M, I, L, A = ms.joint_schedule(g, ms.Warps(1, blocking=blocking))
+    assert I == 3
+    assert all((M["ADD"] - M[o]) % I >= ms.duration(g, o) for o in ("GEMM", "EXP"))
+    # two warps: the consumer moves to the other warp and the interval is the tensor core's again
+    M, I, L, A = ms.joint_schedule(g, ms.Warps(2, blocking=blocking))
+    assert I == 2 and A["ADD"] != A["GEMM"] and A["ADD"] != A["EXP"]
+    assert ms.is_valid_assignment(g, M, I, A, ms.Warps(2, blocking=blocking))
+
+
+def test_joint_search_agrees_with_brute_force_on_the_unrolled_constraints():
+    # small graphs, every (M, A) enumerated and checked with the literal, unrolled constraints
+    cases = []
+    g = _blocking_example()
+    cases.append((g, ms.Warps(1, blocking=[("GEMM", "ADD")])))
+    cases.append((g, ms.Warps(2, blocking=[("GEMM", "ADD")])))
+    cases.append((g, ms.Warps(2, blocking=[("GEMM", "ADD")], spillcost={"GEMM": 2})))
+    t = ms.paper_toy()
+    cases.append((t, ms.Warps(2, blocking=[("S", "P"), ("P", "O")])))
+    cases.append((t, ms.Warps(2, regs={"S": 2, "P": 2, "O": 2}, reg_limit=5, spillcost={"S": 1, "P": 1})))
+    cases.append((t, ms.Warps(3, regs={"S": 2, "P": 2, "O": 2}, reg_limit=4, spillcost={"S": 1, "P": 1})))
+    ld = ms.Loop({"TC": 1, "LSU": 1})
+    ld.op("LOAD", "LSU", 1)
+    ld.op("MMA", "TC", 2)
+    ld.dep("LOAD", "MMA")
+    ld.dep("MMA", "MMA", delta=1)
+    cases.append((ld, ms.Warps(2, variable_latency=["LOAD"])))
+    for loop, ws in cases:
+        got = ms.joint_schedule(loop, ws, max_len=7, max_interval=7)
+        want = _brute_force_joint(loop, ws, max_len=7, max_interval=7)
+        assert (got is None) == (want is None)
+        if got is not None:
+            M, I, L, A = got
+            assert (I, L) == want, (I, L, want)
+            assert _unrolled_ok(loop, M, I, A, ws)
+
+
+def test_variable_latency_operations_get_the_designated_warp_to_themselves():
+    g = ms.Loop({"TC": 1, "LSU": 1, "EXP": 1})
+    g.op("LOAD", "LSU", 1)
+    g.op("MMA", "TC", 2)
+    g.op("EXP", "EXP", 1)
+    g.dep("LOAD", "MMA")
+    g.dep("MMA", "EXP")
+    ws = ms.Warps(3, variable_latency=["LOAD"], spillcost={"MMA": 2})
+    M, I, L, A = ms.joint_schedule(g, ws)
+    assert A["LOAD"] == 0 and A["MMA"] != 0 and A["EXP"] != 0
+    assert A["MMA"] == A["EXP"]                  # a third warp would cost the transfer of MMA's result
+    bad = dict(A, EXP=0)                          # a fixed-latency operation on W_vl is not allowed
+    assert not ms.is_valid_assignment(g, M, I, bad, ws)
+    # with a single warp there is no W_vl to give: unsatisfiable (Section 5.1 relaxes such problems)
+    assert ms.joint_schedule(g, ms.Warps(1, variable_latency=["LOAD"]), max_interval=6) is None
+
+
+def test_register_limit_forces_a_partition_and_the_transfer_is_paid():
+    g = ms.paper_toy()
+    regs = {"S": 100, "P": 100, "O": 100}
+    # everything on one warp needs up to 400 registers at once (two S, P and O overlap, see above)
+    one = ms.Warps(1, regs=regs, reg_limit=400)
+    M, I, L, A = ms.joint_schedule(g, one)
+    assert (I, L) == (2, 4)
+    # 255 per warp: no single warp can hold it; spread over warps, every crossing edge pays the transfer
+    ws = ms.Warps(3, regs=regs, reg_limit=255, spillcost={"S": 1, "P": 1})
+    assert ms.joint_schedule(g, ms.Warps(1, regs=regs, reg_limit=255), max_interval=8) is None
+    M, I, L, A = ms.joint_schedule(g, ws)
+    assert len(set(A.values())) >= 2 and I == 2 and L >= 4
+    assert ms.is_valid_assignment(g, M, I, A, ws) and _unrolled_ok(g, M, I, A, ws)
+    for u, v, d, delta in g.edges:
+        if A[u] != A[v]:
+            assert M[v] + I * delta >= M[u] + d + ws.spillcost[u]
+
+
+def test_gfx950_attention_needs_no_warp_specialisation():
+    # The loop this library runs, with the measured gfx950 costs.  Its global->LDS loads are streaming
+    # operations several tiles ahead (zero latency in the model, Section 5.3), MFMA results reach the VALU
+    # through fixed-latency interlocks rather than blocking waits, and the three-stage schedule keeps every
+    # wait satisfied before it is reached: no variable-latency operation, no blocking edge.
+    g, c, _ = ms.gfx950_attention(U=12)
+    regs = dict(ms.GFX950_D128_REGS)
+    free = 256 - ms.GFX950_D128_RESIDENT
+    plain = ms.schedule(g, max_len=4 * sum(c.values()))
+    # handing S or P to another wavefront goes through LDS: a write and a read of the tile, about the cost
+    # of the operand reads of one product in normalised cycles
+    spill = {"QK": c["LDS_K"] + c["LDS_V"], "SM": c["LDS_K"] + c["LDS_V"], "LDS_K": 1, "LDS_V": 1}
+    M, I, L, A = ms.joint_schedule(g, ms.Warps(2, regs=regs, reg_limit=free, spillcost=spill),
+                                   max_len=plain[2] + 4, max_interval=plain[1] + 3)
+    assert (I, L) == (plain[1], plain[2]) and I == c["QK"] + c["PV"]
+    assert len(set(A.values())) == 1             # the joint optimum is the single-wavefront schedule
+    assert max(ms.live_footprint(g, M, I, regs)) <= free
+    # with fewer registers per wavefront (more wavefronts per SIMD) the loop no longer fits one of them:
+    # the model first moves the second product and its accumulators to another wavefront and pays the
+    # transfer of P, then has to give up the matrix pipe's interval as well
+    M2, I2, L2, A2 = ms.joint_schedule(g, ms.Warps(2, regs=regs, reg_limit=100, spillcost=spill),
+                                       max_len=plain[2] + 4, max_interval=plain[1] + 3)
+    assert len(set(A2.values())) == 2 and A2["PV"] != A2["SM"] and I2 == I
+    M3, I3, L3, A3 = ms.joint_schedule(g, ms.Warps(2, regs=regs, reg_limit=68, spillcost=spill),
+                                       max_len=plain[2] + 4, max_interval=plain[1] + 3)
+    assert len(set(A3.values())) == 2 and I3 > I
