@@ -396,6 +396,42 @@ def joint_schedule(loop, ws, max_len=None, max_interval=None):
     return None
 
 
+def swp_and_ws(loop, ws, I, L):
+    """One solve of the joint constraint system at a fixed initiation interval and schedule length bound:
+    (M, A) with length(M) <= L, fewest warps first, or None (the paper hands this step to an SMT solver;
+    the graphs here are small enough to enumerate)."""
+    for A in sorted(_assignments(loop, ws), key=lambda A: len(set(A.values()))):
+        edges = warp_edges(loop, A, ws)
+        blocked = {v for u, v, _, _ in loop.edges if (u, v) in ws.blocking or A[u] != A[v]}
+        for length_ in range(1, L + 1):
+            M = _search(loop, I, length_, edges, lambda M: is_valid_assignment(loop, M, I, A, ws), A, blocked)
+            if M is not None:
+                return M, A
+    return None
+
+
+def search_procedure(loop, ws, max_interval=64):
+    """The search of Section 5.1 (its algorithm listing), step for step: for I = 1, 2, ... take the optimal
+    plain modulo schedule M at I (skip I if there is none); starting from L = len(M), try the joint system
+    at (I, L) and lengthen L by one on failure, but only while that keeps the number of overlapped copies
+    ceil(L / I) of the plain schedule; then move on to I + 1.  Returns (M*, I, A*) or None.
+
+    Unlike joint_schedule it never trades a deeper pipeline for a smaller I: a schedule that needs one more
+    overlapped copy than the plain optimum is passed over in favour of the next interval."""
+    total = sum(duration(loop, v) for v in loop.rrt)
+    for I in range(1, max_interval + 1):
+        M = optimal_modulo_schedule(loop, I, 2 * total + I)
+        if M is None:
+            continue
+        L = base = length(loop, M)
+        while math.ceil(L / I) == math.ceil(base / I):
+            got = swp_and_ws(loop, ws, I, L)
+            if got is not None:
+                return got[0], I, got[1]
+            L += 1
+    return None
+
+
 # ------------------------------------------------------------------ the paper's running example
 def paper_toy():
     """Fig. 1: S = gemm(Q,K) on the tensor core, P = exp(S) on the exp unit, O += gemm(P,V) on the

@@ -326,3 +326,30 @@ def test_gfx950_attention_needs_no_warp_specialisation():
     M3, I3, L3, A3 = ms.joint_schedule(g, ms.Warps(2, regs=regs, reg_limit=68, spillcost=spill),
                                        max_len=plain[2] + 4, max_interval=plain[1] + 3)
     assert len(set(A3.values())) == 2 and I3 > I
+
+
+def test_search_procedure_follows_section_5_1():
+    # where the plain optimum already satisfies the joint system, the procedure returns it at once
+    t = ms.paper_toy()
+    M, I, A = ms.search_procedure(t, ms.Warps(1))
+    assert I == 2 and ms.length(t, M) == 4 and ms.is_valid_assignment(t, M, I, A, ms.Warps(1))
+    # the blocking example: one warp cannot hold I = 2 at any length, so the procedure moves to I = 3;
+    # two warps solve it at I = 2, as the exhaustive joint search found
+    g = _blocking_example()
+    one, two = ms.Warps(1, blocking=[("GEMM", "ADD")]), ms.Warps(2, blocking=[("GEMM", "ADD")])
+    assert ms.search_procedure(g, one)[1] == 3 == ms.joint_schedule(g, one)[1]
+    assert ms.search_procedure(g, two)[1] == 2 == ms.joint_schedule(g, two)[1]
+    # lengthening is allowed only while the number of overlapped copies stays that of the plain schedule.
+    # Here every warp can hold one value at a time and each hand-over costs a cycle: S stays live for three
+    # cycles, so I >= 3, and at I = 3 the schedule is S 0, P 2, O 4 (L = 5, two overlapped copies).  The
+    # plain optimum at I = 3 has L = 3 (one copy), so the procedure may not lengthen to 5 there, nor at
+    # I = 4; it settles at I = 5, where L = 5 is still one copy.  The exhaustive search takes I = 3.
+    regs = {"S": 100, "P": 100, "O": 100}
+    ws = ms.Warps(3, regs=regs, reg_limit=150, spillcost={"S": 1, "P": 1})
+    Mj, Ij, Lj, Aj = ms.joint_schedule(t, ws)
+    Mp, Ip, Ap = ms.search_procedure(t, ws)
+    assert (Ij, Lj) == (3, 5) and (Ip, ms.length(t, Mp)) == (5, 5)
+    assert ms.is_valid_assignment(t, Mp, Ip, Ap, ws) and _unrolled_ok(t, Mp, Ip, Ap, ws)
+    assert _unrolled_ok(t, Mj, Ij, Aj, ws)
+    plain = ms.optimal_modulo_schedule(t, Ip, 12)
+    assert math.ceil(ms.length(t, Mp) / Ip) == math.ceil(ms.length(t, plain) / Ip) == 1
