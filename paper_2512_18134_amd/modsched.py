@@ -191,29 +191,38 @@ def duration(loop, v):
     return max(1, len(loop.rrt[v]))
 
 
-def live_ranges(loop, M, I):
-    """[start, end) of the result of one instance of every instruction, in the time of its own iteration:
-    reserved from the cycle the instruction issues until its last consumer (u, delta) has finished, i.e.
-    cycle M[u] + I*delta + duration(u).  A result nobody consumes dies when its instruction finishes.
-    A loop-carried self edge (an accumulator updated in place: O += ...) hands its registers to the next
-    instance when that instance issues.  (The paper states liveness as backward dataflow constraints over
-    the unrolled schedule; for a fixed (M, I) those constraints have this closed form.)"""
+def live_ranges(loop, M, I, release="finish"):
+    """[start, end) of the result of one instance of every instruction, in the time of its own iteration.
+
+    release="issue" is the paper's definition (Section 4.2: backward dataflow over the unrolled schedule --
+    a result becomes live in the cycle its instruction issues and dies in the cycle its last user (u, delta)
+    issues, M[u] + I*delta; a result nobody uses is never live).  For a fixed (M, I) those constraints have
+    this closed form; tests check it against the dataflow written out.
+
+    release="finish" (default, what the gfx950 register budgets use) keeps a result reserved until its last
+    user has FINISHED, M[u] + I*delta + duration(u): a tile-level instruction here is a run of MFMAs or
+    VALU operations that reads its operand registers throughout, so they cannot be handed on at its issue.
+    A result nobody uses then dies when its own instruction finishes.
+
+    Either way a loop-carried self edge (an accumulator updated in place: O += ...) hands its registers to
+    the next instance when that instance issues."""
+    assert release in ("issue", "finish")
     out = {}
     for v in M:
-        end = M[v] + duration(loop, v)
+        end = M[v] + duration(loop, v) if release == "finish" else M[v]
         for u, w, d, delta in loop.edges:
             if u == v and w == v:
                 end = max(end, M[v] + I * delta)
             elif u == v:
-                end = max(end, M[w] + I * delta + duration(loop, w))
+                end = max(end, M[w] + I * delta + (duration(loop, w) if release == "finish" else 0))
         out[v] = (M[v], end)
     return out
 
 
-def live_footprint(loop, M, I, footprint, resident=0):
+def live_footprint(loop, M, I, footprint, resident=0, release="finish"):
     """Steady-state memory use per cycle (mod I): sum over instructions of footprint x number of
     overlapped iterations whose instance is live at that cycle, plus `resident` (loop invariants)."""
-    ranges = live_ranges(loop, M, I)
+    ranges = live_ranges(loop, M, I, release)
     use = [resident] * I
     for v, (a, b) in ranges.items():
         f = footprint.get(v, 0)
@@ -224,9 +233,9 @@ def live_footprint(loop, M, I, footprint, resident=0):
     return use
 
 
-def fits(loop, M, I, footprint, capacity, resident=0):
+def fits(loop, M, I, footprint, capacity, resident=0, release="finish"):
     """The paper's Memory Capacity constraint for one memory (here: the register file of a wave)."""
-    return max(live_footprint(loop, M, I, footprint, resident)) <= capacity
+    return max(live_footprint(loop, M, I, footprint, resident, release)) <= capacity
 
 
 # ------------------------------------------------------------------ warp assignment (Section 4.3)

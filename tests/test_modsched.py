@@ -353,3 +353,68 @@ def test_search_procedure_follows_section_5_1():
     assert _unrolled_ok(t, Mj, Ij, Aj, ws)
     plain = ms.optimal_modulo_schedule(t, Ip, 12)
     assert math.ceil(ms.length(t, Mp) / Ip) == math.ceil(ms.length(t, plain) / Ip) == 1
+
+
+# ------------------------------------------------------------------ liveness as the paper states it
+def _dataflow_footprint(loop, M, I, footprint):
+    """Section 4.2 written out: a straight-line program of overlapped copies of M, I cycles apart, T cycles
+    long; live[v, i, t] from the backward dataflow constraints (Init, LiveProp-1/2, DeadProp-1/2); the
+    Memory Capacity sum per cycle.  The paper's Q executes the steady state once (ceil(L/I) copies); here
+    a few more copies are laid out, so that one interval in the middle has every neighbour it has in the
+    running loop (in Q itself the first steady cycles lack the loop-carried values of the copies before
+    them).  Returns the use in that interval.  Independent of ms.live_ranges: no closed form, only the
+    propagation rules."""
+    L = ms.length(loop, M)
+    max_delta = max([dl for _, _, _, dl in loop.edges] + [0])
+    k = math.ceil(L / I) + max_delta + 1                 # the interval [k*I, (k+1)*I) is looked at
+    copies = k + math.ceil(L / I) + max_delta + 2
+    T = (copies - 1) * I + L
+    op = lambda v, i, t: 0 <= i < copies and t == M[v] + i * I
+    users = {v: [(u, dl) for a, u, _, dl in loop.edges if a == v] for v in M}
+    live = {}
+    for v in M:
+        for i in range(copies):
+            # Init: only loop-carried results of the last copy are live at the last cycle
+            live[(v, i, T)] = i == copies - 1 and any(dl > 0 for _, dl in users[v])
+    for t in range(T, 0, -1):
+        for v in M:
+            for i in range(copies):
+                if live[(v, i, t)]:
+                    live[(v, i, t - 1)] = not op(v, i, t)                        # LiveProp-1 / LiveProp-2
+                else:
+                    live[(v, i, t - 1)] = any(op(u, i + dl, t) for u, dl in users[v])   # DeadProp-1 / -2
+    return [sum(footprint.get(v, 0) for v in M for i in range(copies) if live[(v, i, t)])
+            for t in range(k * I, (k + 1) * I)]
+
+
+def test_closed_form_liveness_is_the_papers_dataflow():
+    import random
+    rnd = random.Random(5)
+    t = ms.paper_toy()
+    M, I = {"S": 0, "P": 2, "O": 3}, 2
+    fp = {"S": 1, "P": 1, "O": 1}
+    # the paper's rule: S is live from its issue until P issues, P until O issues, O one interval
+    assert ms.live_ranges(t, M, I, release="issue") == {"S": (0, 2), "P": (2, 3), "O": (3, 5)}
+    assert _dataflow_footprint(t, M, I, fp) == ms.live_footprint(t, M, I, fp, release="issue") == [3, 2]
+    # holding operands until the consumer has finished (what the register budgets here use) costs one more
+    assert ms.live_footprint(t, M, I, fp) == [4, 3]
+    # random small loops and their optimal schedules
+    checked = 0
+    while checked < 60:
+        n = rnd.randint(2, 4)
+        g = ms.Loop({"A": 2, "B": 1})
+        names = ["v%d" % k for k in range(n)]
+        for v in names:
+            g.op(v, rnd.choice(["A", "B"]), rnd.randint(1, 2))
+        for a in range(n):
+            for b in range(a + 1, n):
+                if rnd.random() < 0.6:
+                    g.dep(names[a], names[b])
+        if rnd.random() < 0.7:
+            g.dep(names[-1], names[-1], delta=1)
+        if rnd.random() < 0.3:
+            g.dep(names[-1], names[0], d=0, delta=2)
+        M, I, L = ms.schedule(g, max_len=12)
+        fp = {v: rnd.randint(1, 3) for v in names}
+        assert _dataflow_footprint(g, M, I, fp) == ms.live_footprint(g, M, I, fp, release="issue"), (M, I, g.edges)
+        checked += 1
