@@ -164,10 +164,15 @@ def pipeline_code(loop, M, I):
             "prologue": prologue, "steady": [(c, v, k) for c, v, k in steady]}
 
 
-def normalise_costs(C, U):
-    """Section 5.2: integers C' (sum in [1, U]) minimising F with |C[i]C'[j] - C[j]C'[i]| <= F for all i, j.
+def normalise_costs(C, U, objective="relative"):
+    """Section 5.2: integers C' with 1 <= sum(C') <= U and |C[i]C'[j] - C[j]C'[i]| <= F for all i, j.
 
-    Exhaustive over the scale of the largest entry (every optimum has C' close to a scaled C)."""
+    objective="paper" minimises F itself, as the section's ILP states (ties: the finer resolution).  F grows
+    with the magnitude of C', so that objective leans towards coarse solutions ([100, 101] with U = 15 gives
+    [1, 1], F = 1, rather than [7, 7], F = 7: the same ratios); objective="relative" (default) minimises
+    F / sum(C'), the ratio error at the scale of the solution, which keeps the resolution U pays for.
+    Returns (C', F).  Candidates: every scale of the largest entry, each other entry rounded down or up."""
+    assert objective in ("relative", "paper")
     n = len(C)
     big = max(range(n), key=lambda i: C[i])
     best = None
@@ -179,8 +184,7 @@ def normalise_costs(C, U):
             if not (1 <= sum(cand) <= U):
                 continue
             F = max(abs(C[i] * cand[j] - C[j] * cand[i]) for i in range(n) for j in range(n))
-            # prefer smaller F relative to the scale (F grows with the scale), then finer resolution
-            key = (F / max(1, sum(cand)), -sum(cand))
+            key = (F / max(1, sum(cand)), -sum(cand)) if objective == "relative" else (F, -sum(cand))
             if best is None or key < best[0]:
                 best = (key, list(cand), F)
     return best[1], best[2]

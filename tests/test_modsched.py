@@ -418,3 +418,25 @@ def test_closed_form_liveness_is_the_papers_dataflow():
         fp = {v: rnd.randint(1, 3) for v in names}
         assert _dataflow_footprint(g, M, I, fp) == ms.live_footprint(g, M, I, fp, release="issue"), (M, I, g.edges)
         checked += 1
+
+
+def test_cost_normalisation_with_the_papers_objective_is_the_global_minimum_of_f():
+    import itertools
+
+    def brute(C, U):
+        best = None
+        for cand in itertools.product(range(U + 1), repeat=len(C)):
+            if 1 <= sum(cand) <= U:
+                F = max(abs(C[i] * cand[j] - C[j] * cand[i]) for i in range(len(C)) for j in range(len(C)))
+                if best is None or (F, -sum(cand)) < best[0]:
+                    best = ((F, -sum(cand)), list(cand), F)
+        return best[1], best[2]
+
+    for C, U in [([512, 790, 512], 10), ([1000, 1000, 500, 250], 12), ([512, 480, 512], 24), ([3, 7, 11], 9),
+                 ([100, 101], 15), ([90, 512, 790, 115, 512], 12), ([5, 5, 9, 2], 14)]:
+        assert ms.normalise_costs(C, U, objective="paper") == brute(C, U), (C, U)
+    # exact ratios are found by both objectives when U allows them
+    assert ms.normalise_costs([1000, 1000, 500, 250], 12, objective="paper") == ([4, 4, 2, 1], 0)
+    # absolute F leans towards coarse solutions, the relative objective keeps the resolution
+    assert ms.normalise_costs([100, 101], 15, objective="paper") == ([1, 1], 1)
+    assert ms.normalise_costs([100, 101], 15) == ([7, 7], 7)
