@@ -116,3 +116,27 @@ def test_backward_every_element(B, case):
         assert torch.isfinite(got[n].float()).all(), name
         print("%s %s max error %.3e (bar %.3e)" % (case[:6], name, err[n], rel * top[n] + 2e-5), flush=True)
         assert err[n] <= rel * top[n] + 2e-5, name
+
+
+def _random_cases(n, seed):
+    import numpy as np
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128, 128, 256]))
+        dt = BF if rng.random() < 0.5 else HF
+        b, h = int(rng.integers(1, 4)), int(rng.integers(1, 13))
+        sq, skv = int(rng.integers(300, 5000)), int(rng.integers(300, 5000))
+        if rng.random() < 0.5:
+            skv = sq
+        out.append((b, h, sq, skv, d, bool(rng.integers(0, 2)), dt))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_cases(40, seed=31), ids=lambda c: "B%d_H%d_Sq%d_Skv%d_D%d_%s_%s" % (
+    c[0], c[1], c[2], c[3], c[4], "causal" if c[5] else "full", "bf16" if c[6] == BF else "f16"))
+def test_random_mid_size_shapes_every_element(B, case):
+    # lengths of 300-5000 (many tiles, ragged tails, S_q != S_kv), too large for the oracle to take whole
+    test_forward_every_element(B, case)
+    if case[4] <= 128:
+        test_backward_every_element(B, case)
