@@ -125,12 +125,15 @@ long long attn_fwd_splitkv_workspace_bytes(int B, int H, int S_q, int D, int n_s
 /*
  * Diagnostic, host only (no GPU call): which (head, tile) the workgroup with id `workgroup` of a launch of
  * n_heads * n_tiles workgroups works on -- the work decomposition of the kernels (XCD-aware; causal:
- * heaviest tiles first, in groups of heads that share an L2).  `*head` = b*H + h, `*tile` = index of the
- * tile of owner rows (query tiles in the forward pass; the key-owner backward sweep counts its tiles from
- * the other end).  Returns ATTN_OK, or ATTN_ERR_NULL / ATTN_ERR_SHAPE (n_heads, n_tiles < 1, product above
+ * heaviest tiles first, in groups of heads that share an L2).  `head_bytes`: bytes of operands the
+ * workgroups of one head stream (forward: K and V, 4 * S_kv * D; backward: 4 * (S_q + S_kv) * D); it sizes
+ * the causal groups and is ignored otherwise.  `*head` = b*H + h, `*tile` = index of the tile of owner rows
+ * (query tiles in the forward pass; the key-owner backward sweep counts its tiles from the other end).
+ * Returns ATTN_OK, or ATTN_ERR_NULL / ATTN_ERR_SHAPE (n_heads, n_tiles < 1, head_bytes < 0, product above
  * 2^31 - 1, workgroup outside [0, n_heads * n_tiles)).
  */
-int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, int *head, int *tile);
+int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, long long head_bytes,
+                        int *head, int *tile);
 
 /* Static, NUL-terminated description of an attn_status value; never freed. */
 const char *attn_strerror(int status);

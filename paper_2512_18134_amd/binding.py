@@ -37,7 +37,7 @@ _lib.attn_strerror.argtypes = [ctypes.c_int]
 _lib.attn_version.restype = ctypes.c_int
 _lib.attn_version.argtypes = []
 _lib.attn_workgroup_tile.restype = ctypes.c_int
-_lib.attn_workgroup_tile.argtypes = [ctypes.c_int] * 4 + [ctypes.POINTER(ctypes.c_int)] * 2
+_lib.attn_workgroup_tile.argtypes = [ctypes.c_int] * 4 + [ctypes.c_longlong] + [ctypes.POINTER(ctypes.c_int)] * 2
 
 ATTN_OK = 0
 ATTN_ERR_NULL = -1
@@ -64,10 +64,10 @@ def attn_version():
     return int(_lib.attn_version())
 
 
-def attn_workgroup_tile(causal, workgroup, n_heads, n_tiles):
+def attn_workgroup_tile(causal, workgroup, n_heads, n_tiles, head_bytes=0):
     """attn_workgroup_tile (host-only diagnostic): the (head, tile) that workgroup id works on."""
     head, tile = ctypes.c_int(-1), ctypes.c_int(-1)
-    rc = int(_lib.attn_workgroup_tile(int(bool(causal)), int(workgroup), int(n_heads), int(n_tiles),
+    rc = int(_lib.attn_workgroup_tile(int(bool(causal)), int(workgroup), int(n_heads), int(n_tiles), int(head_bytes),
                                       ctypes.byref(head), ctypes.byref(tile)))
     if rc != ATTN_OK:
         raise AttnError(rc)

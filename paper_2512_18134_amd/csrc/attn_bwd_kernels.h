@@ -111,7 +111,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_sweep_kernel(const BwdParams
     // ---- workgroup -> (head, owner tile).  Causal: a query tile streams more keys the later it is,
     // a key tile streams more queries the earlier it is; heaviest first either way.
     int bh, ot;
-    wg_to_tile_n<CAUSAL>(blockIdx.x, p.total_wg, p.n_t, bh, ot);
+    // a head's sweeps stream Q, dO, K and V between them
+    wg_to_tile_n<CAUSAL>(blockIdx.x, p.total_wg, p.n_t, 4ll * (p.S_q + p.S_kv) * D, bh, ot);
     if (CAUSAL && KEY_OWNER)
         ot = p.n_t - 1 - ot;
     const int S_own = KEY_OWNER ? p.S_kv : p.S_q;

@@ -52,8 +52,22 @@ __host__ __device__ __forceinline__ int xcd_remap(int wid, int total)
     return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + slot;
 }
 
-// Causal launches: workgroups per XCD that are handed out as one heaviest-first group (2 per CU).
-constexpr int kCausalGroupWgs = 64;
+// Causal launches hand out an XCD's workgroups in heaviest-first groups of whole heads: between 32
+// workgroups (one per CU of the XCD) and 128, as many heads as stream no more than one L2 (4 MB) of
+// operands between them; heads whose operands do not fit an L2 twice over share it by streaming in step
+// instead, and get the large groups (better pairing of heavy and light tiles).
+constexpr int kCausalGroupMinWgs = 32, kCausalGroupMaxWgs = 128;
+constexpr long long kXcdL2Bytes = 4ll << 20;
+
+// heads per group for tiles of n_t per head whose workgroups stream head_bytes of operands per head
+__host__ __device__ __forceinline__ int causal_group_heads(int n_t, long long head_bytes)
+{
+    const int lo = (kCausalGroupMinWgs + n_t - 1) / n_t, hi = (kCausalGroupMaxWgs + n_t - 1) / n_t;
+    const long long fit = head_bytes > 0 ? kXcdL2Bytes / head_bytes : hi;
+    if (fit < 2)
+        return hi;
+    return fit < lo ? lo : (fit > hi ? hi : (int)fit);
+}
 
 // Kernel parameters (plain struct, passed by value).
 struct Params {
@@ -77,13 +91,14 @@ struct Params {
 //  * causal: query tile qt streams ~(qt + 1) times as many K/V tiles as tile 0, and a CU holds one
 //    workgroup at a time, so the dispatch order decides the balance: tiles are handed out heaviest
 //    first (a CU that finishes a light tile of the first batch then picks up the heaviest one left).
-//    Every XCD owns whole heads (K/V stay in one L2) and works through them in groups of enough
-//    heads for at least 64 workgroups -- two per CU of the XCD, so that heavy and light tiles pair up --
-//    heaviest first across the heads of a group: the workgroups in flight on an XCD then stream the
-//    K/V of one or two heads, not of every head the XCD owns, and keep hitting its L2.  When B*H is
-//    not a multiple of the XCD count, the heads left over are shared out tile by tile first.
+//    Every XCD owns whole heads (K/V stay in one L2) and works through them in groups of heads
+//    (causal_group_heads: sized so that the operands of the heads in flight fit the L2, and so that
+//    heavy and light tiles pair up), heaviest first across the heads of a group.  When B*H is not a
+//    multiple of the XCD count, the heads left over are shared out tile by tile first.
+//    head_bytes: operand bytes one head's workgroups stream (forward: K and V).
 template <bool CAUSAL>
-__host__ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int n_t, int &bh, int &t)
+__host__ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int n_t, long long head_bytes, int &bh,
+                                                      int &t)
 {
     if (!CAUSAL) {
         const int logical = xcd_remap(wid, total_wg);
@@ -108,9 +123,9 @@ __host__ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int
         return;
     }
     i -= m_x;
-    // groups of at least `want` heads (64 workgroups), sizes as even as possible, larger ones first:
-    // a short group at the end of the queue would leave its heavy tiles without light partners
-    const int want = (kCausalGroupWgs + n_t - 1) / n_t;
+    // groups of at least `want` heads, sizes as even as possible, larger ones first: a short group at
+    // the end of the queue would leave its heavy tiles without light partners
+    const int want = causal_group_heads(n_t, head_bytes);
     const int ng = a > want ? a / want : 1;
     const int base = a / ng, extra = a % ng;     // `extra` groups of base + 1 heads, then groups of base
     const int big = extra * (base + 1) * n_t;
@@ -129,9 +144,10 @@ __host__ __device__ __forceinline__ void wg_to_tile_n(int wid, int total_wg, int
 }
 
 template <bool CAUSAL>
-__device__ __forceinline__ void wg_to_tile(int wid, const Params &p, int &bh, int &qt)
+__device__ __forceinline__ void wg_to_tile(int wid, const Params &p, int D, int &bh, int &qt)
 {
-    wg_to_tile_n<CAUSAL>(wid, p.total_wg, p.n_qt, bh, qt);
+    // one head's workgroups stream its K and V: 2 tensors x S_kv rows x D 16-bit elements
+    wg_to_tile_n<CAUSAL>(wid, p.total_wg, p.n_qt, 4ll * p.S_kv * D, bh, qt);
 }
 
 }  // namespace attn

@@ -320,17 +320,18 @@ extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, fl
     }
 }
 
-extern "C" int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, int *head, int *tile)
+extern "C" int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, long long head_bytes, int *head,
+                                   int *tile)
 {
     if (!head || !tile)
         return ATTN_ERR_NULL;
-    if (n_heads < 1 || n_tiles < 1 || (long long)n_heads * n_tiles > 0x7fffffffLL || workgroup < 0 ||
+    if (n_heads < 1 || n_tiles < 1 || head_bytes < 0 || (long long)n_heads * n_tiles > 0x7fffffffLL || workgroup < 0 ||
         workgroup >= n_heads * n_tiles)
         return ATTN_ERR_SHAPE;
     if (causal)
-        attn::wg_to_tile_n<true>(workgroup, n_heads * n_tiles, n_tiles, *head, *tile);
+        attn::wg_to_tile_n<true>(workgroup, n_heads * n_tiles, n_tiles, head_bytes, *head, *tile);
     else
-        attn::wg_to_tile_n<false>(workgroup, n_heads * n_tiles, n_tiles, *head, *tile);
+        attn::wg_to_tile_n<false>(workgroup, n_heads * n_tiles, n_tiles, head_bytes, *head, *tile);
     return ATTN_OK;
 }
 

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
     const int g = lane >> 5;
 
     int bh, qt;
-    wg_to_tile<CAUSAL>(blockIdx.x, p, bh, qt);
+    wg_to_tile<CAUSAL>(blockIdx.x, p, D, bh, qt);
     const int q0 = qt * BM;
     auto qcol = [&](int qb) { return q0 + (wave * QB + qb) * 32 + lq; };
 

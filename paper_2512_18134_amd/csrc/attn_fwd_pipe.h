@@ -97,7 +97,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pipe_kernel(const Params p)
     const int g = lane >> 5;
 
     int bh, qt;
-    wg_to_tile<CAUSAL>(blockIdx.x, p, bh, qt);
+    wg_to_tile<CAUSAL>(blockIdx.x, p, D, bh, qt);
     const int q0 = qt * BM;
     const int q0w = q0 + wave * 32 * QB;
     auto qcol = [&](int qb) { return q0w + 32 * qb + lq; };  // query row of this lane in block qb

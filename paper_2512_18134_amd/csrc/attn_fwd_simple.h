@@ -39,7 +39,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_simple_kernel(const Params p
 
     // ---- workgroup -> (b*H+h, query tile), XCD-aware, heaviest causal tiles first
     int bh, qt;
-    wg_to_tile<CAUSAL>(blockIdx.x, p, bh, qt);
+    wg_to_tile<CAUSAL>(blockIdx.x, p, D, bh, qt);
 
     const int q0 = qt * BM;
     const int q0w = q0 + wave * 32;

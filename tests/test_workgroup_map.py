@@ -8,7 +8,16 @@ import ctypes
 import pytest
 
 N_XCD = 8
-GROUP_WGS = 64      # workgroups of one causal group per XCD: two per CU
+L2_BYTES = 4 << 20                  # one XCD's L2
+HEAD_BYTES = [0, 256 << 10, 1 << 20, 3 << 20, 64 << 20]
+
+
+def group_heads(n_tiles, head_bytes):
+    """Heads per causal group: between 32 and 128 workgroups, as many heads as stream no more than one L2
+    of operands between them; heads that do not fit an L2 twice over get the large groups."""
+    lo, hi = -(-32 // n_tiles), -(-128 // n_tiles)
+    fit = L2_BYTES // head_bytes if head_bytes else hi
+    return hi if fit < 2 else min(max(fit, lo), hi)
 
 
 @pytest.fixture(scope="module")
@@ -17,8 +26,8 @@ def B():
     return binding
 
 
-def table(B, causal, n_heads, n_tiles):
-    return [B.attn_workgroup_tile(causal, w, n_heads, n_tiles) for w in range(n_heads * n_tiles)]
+def table(B, causal, n_heads, n_tiles, head_bytes=0):
+    return [B.attn_workgroup_tile(causal, w, n_heads, n_tiles, head_bytes) for w in range(n_heads * n_tiles)]
 
 
 SHAPES = [(1, 1), (1, 7), (3, 5), (8, 1), (8, 64), (16, 64), (24, 33), (32, 16), (40, 4), (128, 8), (13, 9),
@@ -29,8 +38,9 @@ SHAPES = [(1, 1), (1, 7), (3, 5), (8, 1), (8, 64), (16, 64), (24, 33), (32, 16),
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "heads%d_tiles%d" % s)
 def test_every_pair_exactly_once(B, causal, shape):
     n_heads, n_tiles = shape
-    t = table(B, causal, n_heads, n_tiles)
-    assert sorted(t) == [(h, q) for h in range(n_heads) for q in range(n_tiles)]
+    for head_bytes in HEAD_BYTES:
+        t = table(B, causal, n_heads, n_tiles, head_bytes)
+        assert sorted(t) == [(h, q) for h in range(n_heads) for q in range(n_tiles)]
 
 
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "heads%d_tiles%d" % s)
@@ -48,17 +58,18 @@ def test_full_attention_gives_each_xcd_a_contiguous_range(B, shape):
     assert all(a[1] + 1 == b[0] for a, b in zip(bounds, bounds[1:]))
 
 
+@pytest.mark.parametrize("head_bytes", HEAD_BYTES, ids=lambda b: "%dKiB" % (b >> 10))
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "heads%d_tiles%d" % s)
-def test_causal_queues(B, shape):
+def test_causal_queues(B, shape, head_bytes):
     # XCD x owns the whole heads x*a .. x*a + a - 1; the n_heads % 8 heads left over are shared out
     # tile by tile and come first in every queue
     n_heads, n_tiles = shape
     a, r = divmod(n_heads, N_XCD)
-    want = -(-GROUP_WGS // n_tiles)                      # heads for 64 workgroups
+    want = group_heads(n_tiles, head_bytes)
     ng = a // want if a > want else 1
     sizes = [a // ng + 1] * (a % ng) + [a // ng] * (ng - a % ng) if a else []
     assert sum(sizes) == a and all(z >= min(want, a) for z in sizes)
-    t = table(B, True, n_heads, n_tiles)
+    t = table(B, True, n_heads, n_tiles, head_bytes)
     left_weight = []
     for x in range(N_XCD):
         queue = t[x::N_XCD]
@@ -89,10 +100,21 @@ def test_causal_queues(B, shape):
 
 
 def test_arguments_are_checked(B):
-    for bad in [(0, 0, 4), (0, 4, 0), (-1, 4, 4), (16, 4, 4), (0, 1 << 16, 1 << 16)]:
+    for bad in [(0, 0, 4), (0, 4, 0), (-1, 4, 4), (16, 4, 4), (0, 1 << 16, 1 << 16), (0, 4, 4, -1)]:
         with pytest.raises(B.AttnError) as e:
             B.attn_workgroup_tile(False, *bad)
         assert e.value.status == B.ATTN_ERR_SHAPE
     lib = ctypes.CDLL(B._lib._name)
-    lib.attn_workgroup_tile.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 2
-    assert lib.attn_workgroup_tile(0, 0, 1, 1, None, None) == B.ATTN_ERR_NULL
+    lib.attn_workgroup_tile.argtypes = [ctypes.c_int] * 4 + [ctypes.c_longlong] + [ctypes.c_void_p] * 2
+    assert lib.attn_workgroup_tile(0, 0, 1, 1, 0, None, None) == B.ATTN_ERR_NULL
+
+
+def test_group_sizes_follow_the_l2(B):
+    # 16 heads per XCD, 4 tiles each (D = 128, S = 1024 forward): K and V of a head are 512 KiB, eight
+    # heads fill the 4 MiB L2 -> groups of 8 heads (32 workgroups); at 4 KiB per head the cap of 128
+    # workgroups decides (32 heads asked, 16 there); heads of 8 MiB cannot share an L2 by fitting and get
+    # the large groups as well
+    for head_bytes, heads in ((512 << 10, 8), (4 << 10, 16), (8 << 20, 16), (1 << 20, 8), (2 << 20, 8)):
+        queue = table(B, True, 128, 4, head_bytes)[0::N_XCD]
+        first_group = {h for h, _ in queue[:heads * 4]}
+        assert len(first_group) == heads and len({h for h, _ in queue[:heads * 4 + 1]}) == heads + (heads < 16)
