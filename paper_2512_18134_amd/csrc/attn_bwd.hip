@@ -2,12 +2,12 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "attn_bwd.h"  // the C declaration (include/)
 #include "attn_bwd_asm.h"
 #include "attn_bwd_kernels.h"
 #include "attn_fwd.h"  // attn_status
+#include "attn_launch.h"
 
 namespace {
 
@@ -21,20 +21,17 @@ int launch_sweep(K kern, BwdParams p, int BH, int S_own, int NW, int lds_bytes, 
     if (total > 0x7fffffffLL)
         return ATTN_ERR_SHAPE;
     p.total_wg = (int)total;
-    if (lds_bytes > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            lds_bytes) != hipSuccess) {
-        (void)hipGetLastError();
+    if (!attn::allow_lds(reinterpret_cast<const void *>(kern), lds_bytes))
         return ATTN_ERR_LAUNCH;
-    }
     hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(NW * 64), lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
-template <int D, int QNW>
-int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
+// plain: run the compiler-scheduled sweeps (always when scale == 0, which the hand-scheduled loops exclude)
+template <int D>
+int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream, bool plain)
 {
-    constexpr int NWK = 4, NWQ = QNW;  // waves per workgroup of the key-owner / query-owner sweep
+    constexpr int NWK = 4, NWQ = 8;  // waves per workgroup of the key-owner / query-owner sweep
     constexpr int LDSK = 2 * 3 * 64 * D * 2 + 3 * NWK * 256, LDSQ = 2 * 3 * 64 * D * 2 + 3 * NWQ * 256;
     {
         const long long blocks = (p.n_rows + (256 / (D / 8)) - 1) / (256 / (D / 8));
@@ -43,40 +40,21 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream)
         if (hipGetLastError() != hipSuccess)
             return ATTN_ERR_LAUNCH;
     }
+    // hand-scheduled sweeps (they need scale > 0), else the compiler-scheduled ones: key owners first
+    const bool hand = !plain && p.scale > 0.f;
+    constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
     int rc;
-    if constexpr (D == 128 || D == 64) {
-        // hand-scheduled key-owner sweep (needs scale > 0); ATTN_BWD_KERNEL=plain (debug only) keeps the
-        // compiler-scheduled one
-        static const bool plain = [] {
-            const char *e = getenv("ATTN_BWD_KERNEL");
-            return e && e[0] == 'p';
-        }();
-        if (!plain && p.scale > 0.f) {
-            constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
-            rc = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true>, p, BH, p.S_kv, 4, LDSA, stream)
-                        : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true>, p, BH, p.S_kv, 4, LDSA, stream);
-        } else {
-            rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream)
-                        : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream);
-        }
-    } else {
+    if (hand)
+        rc = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true>, p, BH, p.S_kv, 4, LDSA, stream)
+                    : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true>, p, BH, p.S_kv, 4, LDSA, stream);
+    else
         rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream)
                     : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream);
-    }
     if (rc != ATTN_OK)
         return rc;
-    if constexpr (D == 128 || D == 64) {
-        // hand-scheduled query-owner sweep; ATTN_BWD_KERNEL=plain (debug only) keeps the compiler-scheduled one
-        static const bool plain_q = [] {
-            const char *e = getenv("ATTN_BWD_KERNEL");
-            return e && e[0] == 'p';
-        }();
-        if (!plain_q && p.scale > 0.f) {
-            constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
-            return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false>, p, BH, p.S_q, 4, LDSA, stream)
-                          : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false>, p, BH, p.S_q, 4, LDSA, stream);
-        }
-    }
+    if (hand)
+        return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false>, p, BH, p.S_q, 4, LDSA, stream)
+                      : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false>, p, BH, p.S_q, 4, LDSA, stream);
     return causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream)
                   : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream);
 }
@@ -136,17 +114,25 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     const int rc = validate_bwd(q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, B, H, S_q, S_kv, D, scale, p);
     if (rc != ATTN_OK)
         return rc;
-    const long long BH = (long long)B * H;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // Debug only: ATTN_BWD_QNW=4 runs the compiler-scheduled query-owner sweep with one wave per SIMD.
-    static const int qnw = [] {
-        const char *e = getenv("ATTN_BWD_QNW");
-        return e ? atoi(e) : 8;
-    }();
-    if (qnw == 4)
-        return D == 64 ? launch_bwd<64, 4>(p, (int)BH, causal, st) : launch_bwd<128, 4>(p, (int)BH, causal, st);
-    return D == 64 ? launch_bwd<64, 8>(p, (int)BH, causal, st) : launch_bwd<128, 8>(p, (int)BH, causal, st);
+    return D == 64 ? launch_bwd<64>(p, B * H, causal, st, false) : launch_bwd<128>(p, B * H, causal, st, false);
 }
+
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+// Test-only entry point of the debug build of the library: attn_bwd on the compiler-scheduled sweeps
+// (the reference of the schedule-equivalence test).
+extern "C" int attn_bwd_plain(const void *q, const void *k, const void *v, const void *o, const void *d_o,
+                              const float *lse, void *dq, void *dk, void *dv, float *delta_ws, int B, int H, int S_q,
+                              int S_kv, int D, int causal, float scale, void *stream)
+{
+    BwdParams p;
+    const int rc = validate_bwd(q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return D == 64 ? launch_bwd<64>(p, B * H, causal, st, true) : launch_bwd<128>(p, B * H, causal, st, true);
+}
+#endif
 
 template <int D>
 static int launch_bwd_f16(const BwdParams &p, int BH, int causal, hipStream_t st)

@@ -26,7 +26,7 @@
 #include <type_traits>
 
 #include "attn_common.h"
-#include "attn_fwd_pipe.h"  // dma16, wait_vmcnt
+#include "attn_dma.h"       // dma16, wait_vmcnt
 
 namespace attn {
 
@@ -43,15 +43,6 @@ struct BwdParams {
     float c;       // scale * log2(e)
     float scale;
 };
-
-// direct global -> LDS load of 4 bytes per lane: LDS address = m0 + lane*4
-__device__ __forceinline__ void dma4(uint32_t lds_addr, const void *base, uint32_t voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory");
-}
 
 // Delta[r] = sum_d dO[r][d] * O[r][d] (fp32) and LSE'[r] = LSE[r] * log2(e).  D/8 lanes per row, 16 bytes per lane.
 template <int D, typename ELEM = bf16_t>

@@ -2,15 +2,14 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
 #include "attn_fwd.h"
 #include "attn_fwd_asm.h"
 #include "attn_fwd_asm2.h"
-#include "attn_fwd_pipe.h"
 #include "attn_fwd_simple.h"
+#include "attn_launch.h"
 #include "attn_splitkv.h"
 
 namespace {
@@ -19,19 +18,7 @@ using attn::Params;
 
 constexpr int kW4MaxKeys = 4096;  // D = 64, causal: up to this many keys the 4-wave workgroups win (measured)
 
-// opt in to more than 64 KB of dynamic LDS when a kernel needs it (gfx950 has 160 KB per CU)
-template <typename K>
-bool allow_lds(K kern, int bytes)
-{
-    if (bytes <= 64 * 1024)
-        return true;
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
-        hipSuccess) {
-        (void)hipGetLastError();
-        return false;
-    }
-    return true;
-}
+using attn::allow_lds;
 
 template <typename K>
 int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStream_t stream)
@@ -41,7 +28,7 @@ int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStre
     if (total > 0x7fffffffLL)
         return ATTN_ERR_SHAPE;
     p.total_wg = (int)total;
-    if (!allow_lds(kern, lds_bytes))
+    if (!allow_lds(reinterpret_cast<const void *>(kern), lds_bytes))
         return ATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(threads), lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
@@ -56,25 +43,12 @@ int launch_simple(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_simple_kernel<D, BN, NW, false>, p, BH, NW * 32, NW * 64, LDS, stream);
 }
 
-template <int D, int BN, int NW, int QB, int PIPE>
-int launch_pipe(const Params &p, int BH, int causal, hipStream_t stream)
-{
-    constexpr int LDS = 6 * BN * D * 2;
-    if (causal)
-        return launch(attn::attn_fwd_pipe_kernel<D, BN, NW, QB, PIPE, true>, p, BH, NW * 32 * QB, NW * 64, LDS, stream);
-    return launch(attn::attn_fwd_pipe_kernel<D, BN, NW, QB, PIPE, false>, p, BH, NW * 32 * QB, NW * 64, LDS, stream);
-}
-
+// w4: -1 = choose, 0 / 1 = 8-wave / 4-wave workgroups (D = 64 only)
 template <int D>
-int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
+int launch_asm(const Params &p, int BH, int causal, hipStream_t stream, int w4 = -1)
 {
     constexpr int LDS = 8 * 64 * D * 2;
     if constexpr (D == 64) {
-        // Debug only: ATTN_FWD_W4=0 / 1 forces 8-wave / 4-wave workgroups.
-        static const int w4 = [] {
-            const char *e = getenv("ATTN_FWD_W4");
-            return e ? atoi(e) : -1;
-        }();
         // Measured: two 4-wave workgroups per CU instead of one 8-wave one change little when every
         // workgroup streams the same number of tiles (-3 % at long S, +-2 % at short S); with a causal mask
         // and few tiles the finer query tiles balance better (+13 % at S = 1024, +4 % at S = 4096).
@@ -108,26 +82,33 @@ int launch_asm2(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_asm2_kernel<D, QB, false, F16>, p, BH, 128 * QB, 256, LDS, stream);
 }
 
-// Debug only: ATTN_FWD_VARIANT picks a tiling / schedule variant of the pipelined kernel.
-template <int D>
-int launch_pipe_variant(int variant, const Params &p, int BH, int causal, hipStream_t stream)
+// the generic kernel: any scale, heads of any size, program order
+int launch_generic(const Params &p, int BH, int D, int causal, hipStream_t st)
 {
-    switch (variant) {
-    case 4:
-        if (D == 128 && p.scale > 0.f)
-            return launch_asm2<128, 2>(p, BH, causal, stream);
-        return launch_pipe<D, 64, 8, 1, 1>(p, BH, causal, stream);
-    case 1:
-        return launch_pipe<D, 64, 8, 1, 1>(p, BH, causal, stream);
-    case 2:
-        return launch_pipe<D, 64, 8, 1, 2>(p, BH, causal, stream);
-    case 3:
-        return launch_pipe<D, 64, 8, 1, 3>(p, BH, causal, stream);
+    switch (D) {
+    case 64:
+        return launch_simple<64, 64, 8>(p, BH, causal, st);
+    case 128:
+        return launch_simple<128, 64, 8>(p, BH, causal, st);
     default:
-        // the hand-scheduled loop masks scores before the multiply by scale*log2e: it needs scale > 0
-        if (p.scale > 0.f)
-            return launch_asm<D>(p, BH, causal, stream);
-        return launch_pipe<D, 64, 8, 1, 1>(p, BH, causal, stream);
+        return launch_simple<256, 32, 4>(p, BH, causal, st);
+    }
+}
+
+// bf16 dispatch.  The hand-scheduled loops set masked scores to -inf before the multiply by
+// scale*log2e (they need scale > 0) and address K/V of one head with 32-bit byte offsets.
+int dispatch_fwd(const Params &p, int BH, int D, int causal, hipStream_t st)
+{
+    const bool asm_ok = p.scale > 0.f && (long long)p.S_kv * D * 2 < (1LL << 31);
+    if (!asm_ok)
+        return launch_generic(p, BH, D, causal, st);
+    switch (D) {
+    case 64:
+        return launch_asm<64>(p, BH, causal, st);
+    case 128:
+        return launch_asm<128>(p, BH, causal, st);
+    default:
+        return launch_asm2<256, 1>(p, BH, causal, st);
     }
 }
 
@@ -198,7 +179,7 @@ static int launch_splitkv(Params &p, int BH, int n_eff, void *o, float *lse, hip
     p.total_wg = (int)total;
     const int lds = 8 * 64 * D * 2;
     auto kern = attn::attn_fwd_asm_kernel<D, false, F16, true>;
-    if (!allow_lds(kern, lds))
+    if (!allow_lds(reinterpret_cast<const void *>(kern), lds))
         return ATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(512), lds, st, p);
     if (hipGetLastError() != hipSuccess)
@@ -287,38 +268,40 @@ extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, fl
                         int S_kv, int D, int causal, float scale, void *stream)
 {
     Params p;
-    {
-        const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
-        if (rc != ATTN_OK)
-            return rc;
-    }
-    const long long BH = (long long)B * H;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
-    // Debug only: ATTN_FWD_KERNEL=simple forces the generic kernel for every shape.
-    static const bool force_simple = [] {
-        const char *e = getenv("ATTN_FWD_KERNEL");
-        return e && e[0] == 's';
-    }();
-    // The pipelined kernel addresses K/V of one head with 32-bit byte offsets.
-    const bool pipe_ok = !force_simple && (D == 64 || D == 128) && ((long long)S_kv * D * 2 < (1LL << 31));
-    static const int variant = [] {
-        const char *e = getenv("ATTN_FWD_VARIANT");
-        return e ? atoi(e) : 0;
-    }();
-    switch (D) {
-    case 64:
-        return pipe_ok ? launch_pipe_variant<64>(variant, p, (int)BH, causal, st)
-                       : launch_simple<64, 64, 8>(p, (int)BH, causal, st);
-    case 128:
-        return pipe_ok ? launch_pipe_variant<128>(variant, p, (int)BH, causal, st)
-                       : launch_simple<128, 64, 8>(p, (int)BH, causal, st);
-    default:
-        if (!force_simple && variant == 0 && scale > 0.f && ((long long)S_kv * D * 2 < (1LL << 31)))
-            return launch_asm2<256, 1>(p, (int)BH, causal, st);
-        return launch_simple<256, 32, 4>(p, (int)BH, causal, st);
-    }
+    const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    return dispatch_fwd(p, B * H, D, causal, static_cast<hipStream_t>(stream));
 }
+
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+// Test-only entry point of the debug build of the library (libmi355attn_debug.so): attn_fwd with the
+// kernel chosen by the caller.  variant 0: as attn_fwd; 1: the generic program-order kernel;
+// 2: D = 128 on the one-wave-per-SIMD tiling (64 query rows per wave); 3 / 4: D = 64 with 8-wave /
+// 4-wave workgroups.  A variant that does not apply to the arguments returns ATTN_ERR_UNSUPPORTED.
+extern "C" int attn_fwd_variant(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H,
+                                int S_q, int S_kv, int D, int causal, float scale, void *stream, int variant)
+{
+    Params p;
+    const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool asm_ok = p.scale > 0.f && (long long)p.S_kv * D * 2 < (1LL << 31);
+    switch (variant) {
+    case 0:
+        return dispatch_fwd(p, B * H, D, causal, st);
+    case 1:
+        return launch_generic(p, B * H, D, causal, st);
+    case 2:
+        return D == 128 && asm_ok ? launch_asm2<128, 2>(p, B * H, causal, st) : ATTN_ERR_UNSUPPORTED;
+    case 3:
+    case 4:
+        return D == 64 && asm_ok ? launch_asm<64>(p, B * H, causal, st, variant - 3) : ATTN_ERR_UNSUPPORTED;
+    }
+    return ATTN_ERR_UNSUPPORTED;
+}
+#endif
 
 extern "C" int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, long long head_bytes, int *head,
                                    int *tile)

@@ -12,7 +12,7 @@
 #pragma once
 #include "attn_common.h"
 #include "attn_fwd_asm.h"   // U32Vec
-#include "attn_fwd_pipe.h"  // dma16, wait_vmcnt
+#include "attn_dma.h"       // dma16, wait_vmcnt
 
 namespace attn {
 
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
     for (int qb = 0; qb < QB; ++qb)
         U32Vec<QB>::set(thr_base_v, qb, (uint32_t)((CAUSAL ? min(qcol(qb), skv_m1) : skv_m1) - 4 * g));
     const float c_log2e = p.c;
-    typename F32Vec<QB>::type m_ref_v, l_a_v, l_b_v;
+    typename F32Vec<QB>::type m_ref_v, l_run_v;
 
     if constexpr (D == 128) {
 #include "generated/attn_loop_d128a.inc"
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void attn_fwd_asm2_kernel(const Params p)
     // ---- epilogue
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float l_lane = F32Vec<QB>::get(l_a_v, qb) + F32Vec<QB>::get(l_b_v, qb);
+        const float l_lane = F32Vec<QB>::get(l_run_v, qb);
         const float l_tot = l_lane + xor32(l_lane);
         const float inv = 1.f / l_tot;
         const int qrow = qcol(qb);

@@ -2,8 +2,10 @@
 // {64,128,256}, causal or not.  It runs the loop of the paper's Fig. 1a in
 // program order (S = QK^T, softmax, O += PV per K/V tile, no software
 // pipelining inside a wave); two wavefronts per SIMD give the hardware
-// something to overlap.  The pipelined kernel (attn_fwd_pipe.h) takes over for
-// the shapes it supports; this one covers everything else.
+// something to overlap.  The hand-scheduled kernels (attn_fwd_asm.h,
+// attn_fwd_asm2.h) take over for the shapes they support; this one covers
+// everything else (scale == 0, heads of K/V of 2 GiB or more) and is the
+// program-order reference of the schedule-equivalence test.
 //
 // Formulation: S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so
 // that a lane owns one query column: row max / row sum are in-lane reductions

@@ -1,0 +1,37 @@
+// attn_launch.h -- host-side launch helper shared by the entry points.
+#pragma once
+#include <stdint.h>
+
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+#include <unordered_map>
+
+namespace attn {
+
+// Opt in to more than 64 KB of dynamic LDS when a kernel needs it (gfx950 has 160 KB per CU).  The
+// attribute belongs to the kernel on a device: it is set on the first launch of that kernel on that
+// device and remembered, so later launches pay a lock and a lookup instead of a runtime call.
+inline bool allow_lds(const void *kern, int bytes)
+{
+    if (bytes <= 64 * 1024)
+        return true;
+    constexpr int kMaxDev = 64;
+    static std::mutex mu;
+    static std::unordered_map<const void *, uint64_t> done;  // kernel -> devices that have the attribute
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev)
+        return false;
+    std::lock_guard<std::mutex> lock(mu);
+    uint64_t &mask = done[kern];
+    if (mask >> dev & 1)
+        return true;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    mask |= 1ull << dev;
+    return true;
+}
+
+}  // namespace attn

@@ -30,12 +30,11 @@ Hazards handled by construction (the assembler inserts no wait states):
 
 usage: gen_attn_bwd_loop.py <kv|q> <D> <out.inc> [bf16|f16]
 """
-import os
 import sys
 
 
 class Gen:
-    def __init__(self, key_owner, D, NF=4, PFD=3, dtype="bf16"):
+    def __init__(self, key_owner, D, NF=4, PFD=3, dtype="bf16", drop=()):
         assert D in (64, 128) and dtype in ("bf16", "f16")
         self.KO = key_owner
         # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
@@ -110,9 +109,10 @@ class Gen:
         self.s_j, self.s_tk = 48, 49
         self.s_ptr1, self.s_ptr2 = 50, 52
         self.s_t2, self.s_t3 = 54, 55
+        self.s_m0 = 56            # m0 of the surrounding code (reserved register: saved and restored here)
         self.lines = []
-        # timing experiments only (results are wrong with any of these set): drop parts of the loop
-        self.exp = set(filter(None, os.environ.get("ATTN_GEN_BWD_EXP", "").split(",")))
+        # timing experiments only (results are wrong with any of these set): parts of the loop to leave out
+        self.exp = set(drop)
 
     # ------------------------------------------------------------------ helpers
     def e(self, s):
@@ -395,6 +395,7 @@ class Gen:
         e = self.e
         e("s_nop 15")
         e("s_nop 7")
+        e("s_mov_b32 s%d, m0" % self.s_m0)
         e("s_mov_b32 s%d, 0" % self.s_j)
         # tiles 0..3 were issued by the prologue: the loop's first load is tile 4 (absolute t_begin + 4)
         e("s_add_i32 s%d, s%d, 4" % (self.s_tk, self.s_tbeg))
@@ -421,6 +422,7 @@ class Gen:
             self.drain(b)
         e("%s:" % L("DONE_"))
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
+        e("s_mov_b32 m0, s%d" % self.s_m0)
         e("s_nop 15")
         e("s_nop 7")
 
@@ -480,7 +482,7 @@ class Gen:
             pinned.update(range(base, base + n))
         clob = ['"memory"', '"vcc"', '"scc"']
         clob += ['"v%d"' % i for i in range(self.NV) if i not in pinned]
-        clob += ['"s%d"' % i for i in range(self.s_j, self.s_t3 + 1)]
+        clob += ['"s%d"' % i for i in range(self.s_j, self.s_m0 + 1)]
         out.append("    : " + ", ".join(outs))
         out.append("    : " + ", ".join(ins))
         out.append("    : " + ", ".join(clob) + ");")
@@ -488,10 +490,19 @@ class Gen:
 
 
 if __name__ == "__main__":
-    # ATTN_GEN_BWD_NF / ATTN_GEN_BWD_PFD (timing experiments): fragment buffers and prefetch distance
-    nf = int(os.environ.get("ATTN_GEN_BWD_NF", "4"))
-    pfd = int(os.environ.get("ATTN_GEN_BWD_PFD", "3"))
-    dtype = sys.argv[4] if len(sys.argv) > 4 else "bf16"
-    text = Gen(sys.argv[1] == "kv", int(sys.argv[2]), NF=nf, PFD=pfd, dtype=dtype).emit_inc()
-    with open(sys.argv[3], "w") as f:
+    # --nf / --pfd / --drop: timing experiments (fragment buffers, prefetch distance, parts left out);
+    # a library build passes none of them
+    args = sys.argv[1:]
+    nf, pfd, drop = 4, 3, ()
+    while len(args) > 3 and args[-2] in ("--nf", "--pfd", "--drop"):
+        if args[-2] == "--nf":
+            nf = int(args[-1])
+        elif args[-2] == "--pfd":
+            pfd = int(args[-1])
+        else:
+            drop = tuple(filter(None, args[-1].split(",")))
+        args = args[:-2]
+    dtype = args[3] if len(args) > 3 else "bf16"
+    text = Gen(args[0] == "kv", int(args[1]), NF=nf, PFD=pfd, dtype=dtype, drop=drop).emit_inc()
+    with open(args[2], "w") as f:
         f.write(text)

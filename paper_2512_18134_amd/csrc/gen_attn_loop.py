@@ -11,14 +11,27 @@ in-order instruction stream per wave,
                                   then the second half of P(j-1) V(j-1)
              LDS reads for MFMA i+PFD (K fragment: ds_read_b128, V^T fragment:
                                   2 x ds_read_b64_tr_b16), a ring of NF buffers
-             ~VPS VALU/transcendental ops of softmax(S(j)): row max first, then
-                                  fma -> exp2 -> row-sum add -> bf16 pack, software
-                                  pipelined over element pairs
+             ~VPS VALU/transcendental ops of softmax(S(j)): fma -> exp2 -> row-sum
+                                  add -> bf16 pack, software pipelined over element
+                                  pairs (no row maximum on this path, see below)
 
 so that the matrix pipe (32 cycles per MFMA) and the VALU run side by side; the
 same stream runs on two waves per SIMD, which fills the remaining bubbles.
 K/V tiles arrive by direct global->LDS loads into 4-stage rings, two tiles
 ahead, with one workgroup barrier per tile.
+
+Online softmax without a per-tile row maximum.  P = exp2(c s - c m_ref) is
+taken against the reference m_ref the row already has; floating point is scale
+invariant, so a reference that lags the true maximum costs no accuracy as long
+as nothing overflows.  The only per-tile test is therefore on the tile's row
+sum (which is needed anyway): if it is not below 2^8 (an element has grown
+too large, has overflowed, or m_ref is still -inf in the first tile) the wave
+leaves the interleaved stream for an out-of-line pass that finds the exact row
+maximum of the tile, moves m_ref there, scales the running sum (and, deferred
+to the end of the iteration, the accumulator) by alpha = exp2(c (m_old - m_new))
+and recomputes the tile's P from its scores, which the fast path leaves intact
+(the exponent arguments go to temporaries).  On N(0,1) inputs this pass runs
+once per workgroup; it replaces 29 of the 140 VALU operations per tile.
 
 The compiler cannot be made to hold this schedule inside 256 VGPRs (it spills),
 so registers are assigned here and the loop is emitted as ONE inline-asm
@@ -35,15 +48,15 @@ Hazards handled by construction (the assembler inserts no wait states):
     replaying the instruction stream (including the reads prefetched for the
     next iteration).
 
-usage: gen_attn_loop.py <D> <out.inc> [bf16|f16] [waves per workgroup: 8|4]
+usage: gen_attn_loop.py <D> <out.inc> [bf16|f16] [waves per workgroup: 8|4] [--pfd N] [--drop part,part]
+(--pfd and --drop exist for timing experiments; a library build passes neither)
 """
-import os
 import struct
 import sys
 
 
 class Gen:
-    def __init__(self, D, NF=4, PFD=3, dtype="bf16", NW=8):
+    def __init__(self, D, NF=4, PFD=3, dtype="bf16", NW=8, drop=()):
         assert D in (64, 128) and dtype in ("bf16", "f16") and NW in (4, 8)
         self.NW = NW                      # waves per workgroup: every wave loads 1/NW of each K/V tile
         self.D = D
@@ -83,8 +96,10 @@ class Gen:
         self.DCH = take(self.NLD)
         self.MREF = take(1)
         self.MRC = take(1)
-        self.LA = take(1)
-        self.LB = take(1)
+        self.L = take(1)                  # running row sum (this lane's half of the keys)
+        self.TLA = take(1)                # row sum of the current tile, two partial sums
+        self.TLB = take(1)
+        self.TP = take(6)                 # exponent / exp temporaries of three element pairs in flight
         self.ALPHA = take(1)
         self.THRB = take(1)
         self.MX0 = take(1)
@@ -106,16 +121,18 @@ class Gen:
         self.s_tk, self.s_tv = 50, 51
         self.s_t0 = 52            # s[52:53] scratch pair
         self.s_t2 = 54
+        self.s_m0 = 55            # m0 of the surrounding code (reserved register: saved and restored here)
         self.lines = []
-        # timing experiments only (results are wrong with any of these set): drop parts of the loop
-        self.exp = set(filter(None, os.environ.get("ATTN_GEN_EXP", "").split(",")))
+        # timing experiments only (results are wrong with any of these set): parts of the loop to leave out
+        self.exp = set(drop)
 
     def tau_bits(self):
-        """Lazy-rescale threshold: P may reach 2^tau before the reference maximum moves (fp16 P must stay
-        below 2^15).  ATTN_GEN_TAU (timing experiments): 24 and 64 measured no faster than 8, also on
-        sharp-softmax inputs, whose running maximum jumps by far more than any threshold."""
-        tau = float(os.environ.get("ATTN_GEN_TAU", "8"))
-        return struct.unpack("<I", struct.pack("<f", tau))[0]
+        """Bound on a lane's row sum over one tile, as fp32 bits: 2^8, so every P of a tile that passes is
+        below 2^8 (inside fp16's range too).  The bound could be far larger without overflow (bf16 has
+        fp32's exponent range), but a small one keeps one-hot rows exact: a key that outgrows the reference
+        by more than a few bits moves the reference onto itself, its P is then exactly 1 and O is exactly
+        its V row; with a lagging reference its P = 2^x would be rounded to bf16 (2^-9 relative)."""
+        return struct.unpack("<I", struct.pack("<f", 2.0 ** 8))[0]
 
     # ------------------------------------------------------------------ helpers
     def e(self, s):
@@ -184,12 +201,9 @@ class Gen:
         ops.append("v_max_f32 v%d, v%d, v%d" % (self.T, self.MX0, self.MX1))
         return ops
 
-    def decide_ops(self, b):
-        """Lane-pair max, new running max, and the branch to the rare rescale path."""
-        T, TMP2, DD = self.T, self.TMP2, self.DD
-        t0 = self.sr(self.s_t0, 2)
-        if "nomax" in self.exp:
-            return ["%s:" % self.lab("RESCRET%d_" % b)]
+    def pairmax_ops(self):
+        """Lane-pair max (the two lanes that hold one query's keys) and the new reference maximum into T."""
+        T, TMP2 = self.T, self.TMP2
         return [
             "v_mov_b32 v%d, v%d" % (TMP2, T),
             "s_nop 1",
@@ -197,25 +211,25 @@ class Gen:
             "s_nop 1",
             "v_max_f32 v%d, v%d, v%d" % (T, T, TMP2),
             "v_max_f32 v%d, v%d, v%d" % (T, T, self.MREF),  # m_new
-            "v_sub_f32 v%d, v%d, v%d" % (DD, T, self.MREF),
-            "v_mul_f32 v%d, s%d, v%d" % (DD, self.s_c, DD),
-            "v_cmp_lt_f32 %s, s%d, v%d" % (t0, self.s_tau, DD),  # (m_new - m_ref) * c > tau ?
-            "s_cmp_lg_u64 %s, 0" % t0,
-            "s_cbranch_scc1 %s" % self.lab("RESC%d_" % b),
-            "%s:" % self.lab("RESCRET%d_" % b),
         ]
 
     def pair_ops(self, S_cur, P_new):
-        """fma -> exp2 -> row-sum add -> bf16 pack over the 16 element pairs, software pipelined."""
+        """fma -> exp2 -> row-sum add -> bf16 pack over the 16 element pairs, software pipelined three deep.
+        The exponent arguments go to the temporaries TP: S_cur stays intact for the out-of-line pass."""
         ops = []
+        def tp(k, i):
+            return self.TP + 2 * (k % 3) + i
         def F(k):
-            return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (S_cur + 2 * k + i, S_cur + 2 * k + i, self.s_c, self.MRC) for i in (0, 1)]
+            return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (tp(k, i), S_cur + 2 * k + i, self.s_c, self.MRC) for i in (0, 1)]
         def E(k):
-            return ["v_exp_f32 v%d, v%d" % (S_cur + 2 * k + i, S_cur + 2 * k + i) for i in (0, 1)]
+            return ["v_exp_f32 v%d, v%d" % (tp(k, i), tp(k, i)) for i in (0, 1)]
         def A(k):
-            return ["v_add_f32 v%d, v%d, v%d" % (self.LA, self.LA, S_cur + 2 * k),
-                    "v_add_f32 v%d, v%d, v%d" % (self.LB, self.LB, S_cur + 2 * k + 1),
-                    "%s v%d, v%d, v%d" % (self.cvt, P_new + k, S_cur + 2 * k, S_cur + 2 * k + 1)]
+            if k == 0:   # the first pair starts the tile's two partial sums
+                acc = ["v_mov_b32 v%d, v%d" % (self.TLA, tp(k, 0)), "v_mov_b32 v%d, v%d" % (self.TLB, tp(k, 1))]
+            else:
+                acc = ["v_add_f32 v%d, v%d, v%d" % (self.TLA, self.TLA, tp(k, 0)),
+                       "v_add_f32 v%d, v%d, v%d" % (self.TLB, self.TLB, tp(k, 1))]
+            return acc + ["%s v%d, v%d, v%d" % (self.cvt, P_new + k, tp(k, 0), tp(k, 1))]
         if "novalu" in self.exp:
             return []
         for t in range(16 + 2):
@@ -225,7 +239,21 @@ class Gen:
                 ops += E(t - 1)
             if 0 <= t - 2 < 16:
                 ops += A(t - 2)
+        ops.append("v_add_f32 v%d, v%d, v%d" % (self.TLA, self.TLA, self.TLB))
         return ops
+
+    def check_ops(self, b):
+        """Tile row sum below the bound?  Otherwise (too large, inf or NaN) take the out-of-line pass."""
+        t0 = self.sr(self.s_t0, 2)
+        if "novalu" in self.exp:
+            return []
+        return [
+            "v_cmp_ngt_f32 %s, s%d, v%d" % (t0, self.s_tau, self.TLA),   # not (bound > sum)
+            "s_cmp_lg_u64 %s, 0" % t0,
+            "s_cbranch_scc1 %s" % self.lab("SLOW%d_" % b),
+            "%s:" % self.lab("SLOWRET%d_" % b),
+            "v_add_f32 v%d, v%d, v%d" % (self.L, self.L, self.TLA),
+        ]
 
     # ------------------------------------------------------------------- DMA
     def dma_fast(self, which, stage):
@@ -320,18 +348,12 @@ class Gen:
         if "nobar" not in self.exp:
             self.e("s_waitcnt vmcnt(%d)" % (2 * NLD))
             self.e("s_barrier")
-        # ---- VALU program, dealt out over the slots
-        a_ops = self.max_ops(S_cur) + self.decide_ops(b)
+        # ---- VALU program, dealt out evenly over the slots; the row-sum test closes the last slot
         b_ops = self.pair_ops(S_cur, P_new)
-        total = len(a_ops) + len(b_ops)
-        quota = -(-total // NM)
-        na = -(-len(a_ops) // quota)                 # slots taken by the max / decision phase
         valu = {}
-        for i in range(na):
-            valu[i] = a_ops[i * len(a_ops) // na:(i + 1) * len(a_ops) // na]
-        nb_slots = NM - na
-        for i in range(nb_slots):
-            valu[na + i] = b_ops[i * len(b_ops) // nb_slots:(i + 1) * len(b_ops) // nb_slots]
+        for i in range(NM):
+            valu[i] = b_ops[i * len(b_ops) // NM:(i + 1) * len(b_ops) // NM]
+        valu[NM - 1] = valu[NM - 1] + self.check_ops(b)
         # ---- K(j+4) -> K stage b, V(j+2) -> V stage (b+2)%4, spread over the first slots
         # (a fast/slow choice must not jump over other slots' work: each tensor's issue is contiguous)
         extra = {}
@@ -375,18 +397,24 @@ class Gen:
             self.e("v_cmp_gt_i32 vcc, %d, v%d" % (const, self.THR))       # key index > limit ?
             self.e("v_cndmask_b32 v%d, v%d, v%d, vcc" % (S_cur + el, S_cur + el, self.NEGINF))
         self.e("s_branch %s" % L("MASKRET%d_" % b))
-        # ---- move the reference maximum: alpha = exp2((m_ref - m_new) c)
-        self.e("%s:" % L("RESC%d_" % b))
+        # ---- the tile's row sum failed the test: exact row maximum of the (intact) scores, move the
+        # reference there (alpha = exp2((m_ref - m_new) c); 0 when m_ref was still -inf), redo the tile's P
+        P_new = self.PB if b % 2 == 0 else self.PA
+        self.e("%s:" % L("SLOW%d_" % b))
+        for ins in self.max_ops(S_cur) + self.pairmax_ops():
+            self.e(ins)
         self.e("v_sub_f32 v%d, v%d, v%d" % (self.DD, self.MREF, self.T))
         self.e("v_mul_f32 v%d, s%d, v%d" % (self.DD, self.s_c, self.DD))
         self.e("v_exp_f32 v%d, v%d" % (self.ALPHA, self.DD))
         self.e("v_mov_b32 v%d, v%d" % (self.MREF, self.T))
         self.e("v_mul_f32 v%d, s%d, v%d" % (self.MRC, self.s_c, self.T))
         self.e("s_nop 1")
-        self.e("v_mul_f32 v%d, v%d, v%d" % (self.LA, self.LA, self.ALPHA))
-        self.e("v_mul_f32 v%d, v%d, v%d" % (self.LB, self.LB, self.ALPHA))
+        self.e("v_mul_f32 v%d, v%d, v%d" % (self.L, self.L, self.ALPHA))
         self.e("s_mov_b32 s%d, 1" % self.s_resc)
-        self.e("s_branch %s" % L("RESCRET%d_" % b))
+        for ins in self.pair_ops(S_cur, P_new):
+            self.e(ins)
+        self.e("s_nop 7")
+        self.e("s_branch %s" % L("SLOWRET%d_" % b))
         # ---- O *= alpha once every MFMA of P(j-1) V(j-1) has been issued and has retired
         self.e("%s:" % L("RESCO%d_" % b))
         self.e("s_nop 15")
@@ -418,9 +446,10 @@ class Gen:
         e = self.e
         e("s_nop 15")
         e("s_nop 7")
+        e("s_mov_b32 s%d, m0" % self.s_m0)
         e("s_mov_b32 s%d, 0" % self.s_j)
         e("s_mov_b32 s%d, 0" % self.s_resc)
-        e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, self.tau_bits()))   # lazy-rescale threshold (log2 units)
+        e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, self.tau_bits()))   # bound on a tile's row sum
         e("s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kbase, 4 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kbase + 1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vbase, 2 * self.TB))
@@ -429,10 +458,9 @@ class Gen:
         e("s_mov_b32 s%d, 2" % self.s_tv)
         for i in range(16):
             e("v_mov_b32 v%d, 0" % (self.PA + i))                # P(-1) = 0
-        e("v_mov_b32 v%d, 0xff800000" % self.MREF)
-        e("v_mov_b32 v%d, 0" % self.MRC)
-        e("v_mov_b32 v%d, 0" % self.LA)
-        e("v_mov_b32 v%d, 0" % self.LB)
+        e("v_mov_b32 v%d, 0xff800000" % self.MREF)              # no reference yet: the first tile's test fails
+        e("v_mov_b32 v%d, 0xff800000" % self.MRC)
+        e("v_mov_b32 v%d, 0" % self.L)
         e("v_mov_b32 v%d, 1.0" % self.ALPHA)
         # operands of the first PFD MFMAs of iteration 0 ("V(-1)" lives in stage 3)
         self.outstanding = []
@@ -449,6 +477,7 @@ class Gen:
             self.drain(b)
         e("%s:" % L("DONE_"))
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
+        e("s_mov_b32 m0, s%d" % self.s_m0)
         e("s_nop 15")
         e("s_nop 7")
 
@@ -469,8 +498,7 @@ class Gen:
         outs.append('"+{%s}"(s_init[0])' % self.vr(self.SA, 16))
         outs.append('"+{%s}"(s_init[1])' % self.vr(self.SA + 16, 16))
         outs.append('"={%s}"(m_ref)' % self.vr(self.MREF))
-        outs.append('"={%s}"(l_a)' % self.vr(self.LA))
-        outs.append('"={%s}"(l_b)' % self.vr(self.LB))
+        outs.append('"={%s}"(l_run)' % self.vr(self.L))
         ins = []
         nq = 4 * KS // 16
         for i in range(nq):
@@ -494,7 +522,7 @@ class Gen:
         for db in range(DB):
             pinned.update(range(self.O + 16 * db, self.O + 16 * db + 16))
         pinned.update(range(self.SA, self.SA + 32))
-        pinned.update([self.MREF, self.LA, self.LB, self.THRB])
+        pinned.update([self.MREF, self.L, self.THRB])
         pinned.update(range(self.Q, self.Q + 4 * KS))
         pinned.update(range(self.KOFF, self.KOFF + KS))
         pinned.update(range(self.VOFF, self.VOFF + 2 * DB))
@@ -503,7 +531,7 @@ class Gen:
         pinned.update(range(self.DCH, self.DCH + self.NLD))
         clob = ['"memory"', '"vcc"', '"scc"']
         clob += ['"v%d"' % i for i in range(self.NV) if i not in pinned]
-        clob += ['"s%d"' % i for i in range(self.s_j, self.s_t2 + 1)]
+        clob += ['"s%d"' % i for i in range(self.s_j, self.s_m0 + 1)]
         out.append("    : " + ", ".join(outs))
         out.append("    : " + ", ".join(ins))
         out.append("    : " + ", ".join(clob) + ");")
@@ -511,9 +539,17 @@ class Gen:
 
 
 if __name__ == "__main__":
-    D = int(sys.argv[1])
-    dtype = sys.argv[3] if len(sys.argv) > 3 else "bf16"
-    nw = int(sys.argv[4]) if len(sys.argv) > 4 else 8
-    text = Gen(D, PFD=int(os.environ.get("ATTN_GEN_PFD", "3")), dtype=dtype, NW=nw).emit_inc()
-    with open(sys.argv[2], "w") as f:
+    args = sys.argv[1:]
+    pfd, drop = 3, ()
+    while len(args) > 2 and args[-2] in ("--pfd", "--drop"):
+        if args[-2] == "--pfd":
+            pfd = int(args[-1])
+        else:
+            drop = tuple(filter(None, args[-1].split(",")))
+        args = args[:-2]
+    D = int(args[0])
+    dtype = args[2] if len(args) > 2 else "bf16"
+    nw = int(args[3]) if len(args) > 3 else 8
+    text = Gen(D, PFD=pfd, dtype=dtype, NW=nw, drop=drop).emit_inc()
+    with open(args[1], "w") as f:
         f.write(text)

@@ -17,9 +17,14 @@ The O accumulators and the Q fragments live in AGPRs (MFMA reads and writes
 them directly); everything the VALU touches (S, P, addresses, state) is in
 VGPRs.  K/V tiles: direct global->LDS loads, 4-stage rings, one barrier per tile.
 
-usage: gen_attn_loop2.py <d128a|d256a> <out.inc>
+The softmax runs without a per-tile row maximum, as in gen_attn_loop.py: P is
+taken against the reference the row already has, the tile's row sum is tested
+against a bound, and a failed test (rare) sends the wave through an out-of-line
+pass that finds the exact maximum, moves the reference and redoes the tile's P
+from its intact scores.
+
+usage: gen_attn_loop2.py <d128a|d256a> <out.inc> [bf16|f16]
 """
-import os
 import struct
 import sys
 
@@ -72,8 +77,10 @@ class Gen:
         self.DCH = take(self.NLD)
         self.MREF = take(QB)
         self.MRC = take(QB)
-        self.LA = take(QB)
-        self.LB = take(QB)
+        self.L = take(QB)                        # running row sums
+        self.TLA = take(QB)                      # row sums of the current tile, two partial sums each
+        self.TLB = take(QB)
+        self.TP = take(6)                        # exponent / exp temporaries of three element pairs in flight
         self.ALPHA = take(QB)
         self.THRB = take(QB)
         self.THR = take(QB)
@@ -95,6 +102,7 @@ class Gen:
         self.s_tk, self.s_tv = 50, 51
         self.s_t0 = 52                           # s[52:53], s[54:55]: compare masks
         self.s_t2 = 56
+        self.s_m0 = 57            # m0 of the surrounding code (reserved register: saved and restored here)
         self.lines = []
 
     # ------------------------------------------------------------------ helpers
@@ -175,11 +183,11 @@ class Gen:
             ops.append("v_max_f32 v%d, v%d, v%d" % (self.T + qb, self.MX + 2 * qb, self.MX + 2 * qb + 1))
         return ops
 
-    def decide_ops(self, b):
-        QB = self.QB
+    def pairmax_ops(self):
+        """Lane-pair max and the new reference maximum into T, for every query block."""
         seqs = []
-        for qb in range(QB):
-            T, TMP2, DD = self.T + qb, self.TMP2 + qb, self.DD + qb
+        for qb in range(self.QB):
+            T, TMP2 = self.T + qb, self.TMP2 + qb
             seqs.append([
                 "v_mov_b32 v%d, v%d" % (TMP2, T),
                 "s_nop 1",
@@ -187,46 +195,58 @@ class Gen:
                 "s_nop 1",
                 "v_max_f32 v%d, v%d, v%d" % (T, T, TMP2),
                 "v_max_f32 v%d, v%d, v%d" % (T, T, self.MREF + qb),
-                "v_sub_f32 v%d, v%d, v%d" % (DD, T, self.MREF + qb),
-                "v_mul_f32 v%d, s%d, v%d" % (DD, self.s_c, DD),
-                "v_cmp_lt_f32 %s, s%d, v%d" % (self.sr(self.s_t0 + 2 * qb, 2), self.s_tau, DD),
             ])
-        ops = []
-        for i in range(len(seqs[0])):
-            for qb in range(QB):
-                ops.append(seqs[qb][i])
-        t0 = self.sr(self.s_t0, 2)
-        if QB == 2:
-            ops.append("s_or_b64 %s, %s, %s" % (t0, t0, self.sr(self.s_t0 + 2, 2)))
-        ops += ["s_cmp_lg_u64 %s, 0" % t0,
-                "s_cbranch_scc1 %s" % self.lab("RESC%d_" % b),
-                "%s:" % self.lab("RESCRET%d_" % b)]
-        return ops
+        return [seqs[qb][i] for i in range(len(seqs[0])) for qb in range(self.QB)]
 
     def pair_ops(self, S_cur, P_new):
+        """fma -> exp2 -> row-sum add -> pack over the element pairs, software pipelined three deep; the
+        exponent arguments go to the temporaries TP, S_cur stays intact for the out-of-line pass."""
         pairs = [(qb, k) for qb in range(self.QB) for k in range(8)]
         def regs(p):
             qb, k = p
             return self.s_reg(S_cur, qb, 0, 2 * k), self.s_reg(S_cur, qb, 0, 2 * k + 1)
-        def F(p):
-            return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (x, x, self.s_c, self.MRC + p[0]) for x in regs(p)]
-        def E(p):
-            return ["v_exp_f32 v%d, v%d" % (x, x) for x in regs(p)]
-        def A(p):
-            e0, e1 = regs(p)
-            qb, k = p
-            return ["v_add_f32 v%d, v%d, v%d" % (self.LA + qb, self.LA + qb, e0),
-                    "v_add_f32 v%d, v%d, v%d" % (self.LB + qb, self.LB + qb, e1),
-                    "v_cvt_pk_%s_f32 v%d, v%d, v%d" % (self.dtype, P_new + qb * 8 + k, e0, e1)]
+        def tp(t, i):
+            return self.TP + 2 * (t % 3) + i
+        def F(t):
+            p = pairs[t]
+            return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (tp(t, i), x, self.s_c, self.MRC + p[0])
+                    for i, x in enumerate(regs(p))]
+        def E(t):
+            return ["v_exp_f32 v%d, v%d" % (tp(t, i), tp(t, i)) for i in (0, 1)]
+        def A(t):
+            qb, k = pairs[t]
+            if k == 0:   # the first pair of a query block starts its two partial sums
+                acc = ["v_mov_b32 v%d, v%d" % (self.TLA + qb, tp(t, 0)), "v_mov_b32 v%d, v%d" % (self.TLB + qb, tp(t, 1))]
+            else:
+                acc = ["v_add_f32 v%d, v%d, v%d" % (self.TLA + qb, self.TLA + qb, tp(t, 0)),
+                       "v_add_f32 v%d, v%d, v%d" % (self.TLB + qb, self.TLB + qb, tp(t, 1))]
+            return acc + ["v_cvt_pk_%s_f32 v%d, v%d, v%d" % (self.dtype, P_new + qb * 8 + k, tp(t, 0), tp(t, 1))]
         ops = []
         n = len(pairs)
         for t in range(n + 2):
             if t < n:
-                ops += F(pairs[t])
+                ops += F(t)
             if 0 <= t - 1 < n:
-                ops += E(pairs[t - 1])
+                ops += E(t - 1)
             if 0 <= t - 2 < n:
-                ops += A(pairs[t - 2])
+                ops += A(t - 2)
+        for qb in range(self.QB):
+            ops.append("v_add_f32 v%d, v%d, v%d" % (self.TLA + qb, self.TLA + qb, self.TLB + qb))
+        return ops
+
+    def check_ops(self, b):
+        """Tile row sums below the bound?  Otherwise (too large, inf or NaN) take the out-of-line pass."""
+        ops = []
+        for qb in range(self.QB):
+            ops.append("v_cmp_ngt_f32 %s, s%d, v%d" % (self.sr(self.s_t0 + 2 * qb, 2), self.s_tau, self.TLA + qb))
+        t0 = self.sr(self.s_t0, 2)
+        if self.QB == 2:
+            ops.append("s_or_b64 %s, %s, %s" % (t0, t0, self.sr(self.s_t0 + 2, 2)))
+        ops += ["s_cmp_lg_u64 %s, 0" % t0,
+                "s_cbranch_scc1 %s" % self.lab("SLOW%d_" % b),
+                "%s:" % self.lab("SLOWRET%d_" % b)]
+        for qb in range(self.QB):
+            ops.append("v_add_f32 v%d, v%d, v%d" % (self.L + qb, self.L + qb, self.TLA + qb))
         return ops
 
     def combine_ops(self, S_nxt):
@@ -319,21 +339,16 @@ class Gen:
         self.e("%s:" % L("MASKRET%d_" % b))
         self.e("s_waitcnt vmcnt(%d)" % (2 * NLD))
         self.e("s_barrier")
-        a_ops = self.max_ops(S_cur) + self.decide_ops(b)
         b_ops = self.pair_ops(S_cur, P_new)
         c_ops = self.combine_ops(S_nxt)
         nc = 4 if c_ops else 0                       # slots reserved at the end for the combine
-        total = len(a_ops) + len(b_ops)
-        quota = -(-total // (NM - nc))
-        na = -(-len(a_ops) // quota)
         valu = {}
-        for i in range(na):
-            valu[i] = a_ops[i * len(a_ops) // na:(i + 1) * len(a_ops) // na]
-        nbs = NM - nc - na
+        nbs = NM - nc
         for i in range(nbs):
-            valu[na + i] = b_ops[i * len(b_ops) // nbs:(i + 1) * len(b_ops) // nbs]
+            valu[i] = b_ops[i * len(b_ops) // nbs:(i + 1) * len(b_ops) // nbs]
         for i in range(nc):
             valu[NM - nc + i] = c_ops[i * len(c_ops) // nc:(i + 1) * len(c_ops) // nc]
+        valu[NM - 1] = valu[NM - 1] + self.check_ops(b)     # the row-sum test closes the last slot
         # the last K Q^T MFMA must be >= 11 wait states before the combine
         assert not c_ops or (self.DB + self.KS) * self.QB <= NM - nc - 3
         extra = {}
@@ -373,8 +388,12 @@ class Gen:
                 self.e("v_cmp_gt_i32 vcc, %d, v%d" % (const, self.THR + qb))
                 self.e("v_cndmask_b32 v%d, v%d, v%d, vcc" % (x, x, self.NEGINF))
         self.e("s_branch %s" % L("MASKRET%d_" % b))
-        # ---- move the reference maximum
-        self.e("%s:" % L("RESC%d_" % b))
+        # ---- a tile row sum failed the test: exact row maxima of the (intact) scores, move the references
+        # there (alpha = exp2((m_ref - m_new) c); 0 when m_ref was still -inf), redo the tile's P
+        P_new = self.PB if b % 2 == 0 else self.PA
+        self.e("%s:" % L("SLOW%d_" % b))
+        for ins in self.max_ops(S_cur) + self.pairmax_ops():
+            self.e(ins)
         for qb in range(QB):
             self.e("v_sub_f32 v%d, v%d, v%d" % (self.DD + qb, self.MREF + qb, self.T + qb))
             self.e("v_mul_f32 v%d, s%d, v%d" % (self.DD + qb, self.s_c, self.DD + qb))
@@ -383,10 +402,12 @@ class Gen:
             self.e("v_mul_f32 v%d, s%d, v%d" % (self.MRC + qb, self.s_c, self.T + qb))
         self.e("s_nop 1")
         for qb in range(QB):
-            self.e("v_mul_f32 v%d, v%d, v%d" % (self.LA + qb, self.LA + qb, self.ALPHA + qb))
-            self.e("v_mul_f32 v%d, v%d, v%d" % (self.LB + qb, self.LB + qb, self.ALPHA + qb))
+            self.e("v_mul_f32 v%d, v%d, v%d" % (self.L + qb, self.L + qb, self.ALPHA + qb))
         self.e("s_mov_b32 s%d, 1" % self.s_resc)
-        self.e("s_branch %s" % L("RESCRET%d_" % b))
+        for ins in self.pair_ops(S_cur, P_new):
+            self.e(ins)
+        self.e("s_nop 7")
+        self.e("s_branch %s" % L("SLOWRET%d_" % b))
         # ---- O *= alpha (accumulators live in AGPRs: read, scale, write back)
         self.e("%s:" % L("RESCO%d_" % b))
         self.e("s_nop 15")
@@ -424,9 +445,14 @@ class Gen:
         QB = self.QB
         e("s_nop 15")
         e("s_nop 7")
+        e("s_mov_b32 s%d, m0" % self.s_m0)
         e("s_mov_b32 s%d, 0" % self.s_j)
         e("s_mov_b32 s%d, 0" % self.s_resc)
-        e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, struct.unpack("<I", struct.pack("<f", float(os.environ.get("ATTN_GEN_TAU", "8"))))[0]))
+        # bound on a lane's row sum over one tile (every P of the tile is then below it); small, so that a
+        # key that outgrows the reference by more than a few bits moves the reference onto itself and its
+        # P is exactly 1 (see gen_attn_loop.py)
+        tau = 2.0 ** 8
+        e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, struct.unpack("<I", struct.pack("<f", tau))[0]))
         e("s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kbase, 4 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kbase + 1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vbase, 2 * self.TB))
@@ -436,10 +462,9 @@ class Gen:
         for i in range(8 * QB):
             e("v_mov_b32 v%d, 0" % (self.PA + i))
         for qb in range(QB):
-            e("v_mov_b32 v%d, 0xff800000" % (self.MREF + qb))
-            e("v_mov_b32 v%d, 0" % (self.MRC + qb))
-            e("v_mov_b32 v%d, 0" % (self.LA + qb))
-            e("v_mov_b32 v%d, 0" % (self.LB + qb))
+            e("v_mov_b32 v%d, 0xff800000" % (self.MREF + qb))      # no reference yet: the first tile's test fails
+            e("v_mov_b32 v%d, 0xff800000" % (self.MRC + qb))
+            e("v_mov_b32 v%d, 0" % (self.L + qb))
             e("v_mov_b32 v%d, 1.0" % (self.ALPHA + qb))
         self.outstanding = []
         g0 = self.groups()
@@ -456,6 +481,7 @@ class Gen:
             self.drain(b)
         e("%s:" % L("DONE_"))
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
+        e("s_mov_b32 m0, s%d" % self.s_m0)
         e("s_nop 15")
         e("s_nop 7")
 
@@ -475,8 +501,7 @@ class Gen:
         for qb in range(QB):
             outs.append('"+{%s}"(s_init[%d])' % (self.vr(self.s_reg(self.SA, qb, 0), 16), qb))
         outs.append('"={%s}"(m_ref_v)' % self.vr(self.MREF, QB))
-        outs.append('"={%s}"(l_a_v)' % self.vr(self.LA, QB))
-        outs.append('"={%s}"(l_b_v)' % self.vr(self.LB, QB))
+        outs.append('"={%s}"(l_run_v)' % self.vr(self.L, QB))
         for i in range(4 * QB * KS // 16):
             ins.append('"{%s}"(q_pack[%d])' % (self.ar(self.Q + 16 * i, 16), i))
         ins.append('"{%s}"(koff_v)' % self.vr(self.KOFF, KS))
@@ -497,12 +522,12 @@ class Gen:
         pinned = set()
         for qb in range(QB):
             pinned.update(range(self.s_reg(self.SA, qb, 0), self.s_reg(self.SA, qb, 0) + 16))
-        for base, n in ((self.MREF, QB), (self.LA, QB), (self.LB, QB), (self.THRB, QB), (self.KOFF, KS),
+        for base, n in ((self.MREF, QB), (self.L, QB), (self.THRB, QB), (self.KOFF, KS),
                         (self.VOFF, 2 * DB), (self.DVOFF, self.NLD), (self.DROW, self.NLD), (self.DCH, self.NLD)):
             pinned.update(range(base, base + n))
         clob = ['"memory"', '"vcc"', '"scc"']
         clob += ['"v%d"' % i for i in range(self.NV) if i not in pinned]
-        clob += ['"s%d"' % i for i in range(self.s_j, self.s_t2 + 1)]
+        clob += ['"s%d"' % i for i in range(self.s_j, self.s_m0 + 1)]
         out.append("    : " + ", ".join(outs))
         out.append("    : " + ", ".join(ins))
         out.append("    : " + ", ".join(clob) + ");")

@@ -265,33 +265,35 @@ def test_non_default_stream(B):
     assert torch.equal(o0, o1) and torch.equal(l0, l1)
 
 
-def test_pipelined_schedule_equals_program_order_kernel(B, tmp_path):
-    # The software-pipelined loop must compute what the loop in program order computes
-    # (the paper's Fig. 1f against Fig. 1a): run the generic, non-pipelined kernel in a child
-    # process (ATTN_FWD_KERNEL=simple is read once per process) and compare.
-    import os
-    import subprocess
-    import sys
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    out = str(tmp_path / "simple.npz")
-    code = (
-        "import sys, numpy as np, torch; sys.path.insert(0, %r)\n"
-        "from paper_2512_18134_amd import binding, synth\n"
-        "res = {}\n"
-        "for D, causal in ((64, False), (128, True), (256, True)):\n"
-        "    q, k, v = synth.make_qkv(1, 2, 700, 700, D, seed=21)\n"
-        "    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)\n"
-        "    o, lse = binding.attn_fwd(dev(q), dev(k), dev(v), causal=causal, scale=synth.default_scale(D))\n"
-        "    torch.cuda.synchronize()\n"
-        "    res['o%%d' %% D] = o.cpu().view(torch.int16).numpy(); res['l%%d' %% D] = lse.cpu().numpy()\n"
-        "np.savez(%r, **res)\n" % (root, out))
-    env = dict(os.environ, ATTN_FWD_KERNEL="simple")
-    subprocess.run([sys.executable, "-c", code], check=True, env=env, timeout=110)
-    ref = np.load(out)
+def test_pipelined_schedule_equals_program_order_kernel(B):
+    # The software-pipelined loop must compute what the loop in program order computes (the paper's
+    # Fig. 1f against Fig. 1a): the generic, non-pipelined kernel runs through the debug build's
+    # attn_fwd_variant entry point on the same inputs.
+    import debug_lib
     for D, causal in ((64, False), (128, True), (256, True)):
         q, k, v = synth.make_qkv(1, 2, 700, 700, D, seed=21)
-        og, lg = run_gpu(B, q, k, v, causal, synth.default_scale(D))
-        o_simple = synth.bf16_bits_to_f32(ref["o%d" % D].view(np.uint16)).astype(np.float64)
+        scale = synth.default_scale(D)
+        og, lg = run_gpu(B, q, k, v, causal, scale)
+        o_s, l_s = debug_lib.attn_fwd_variant(to_dev(q), to_dev(k), to_dev(v), causal, scale,
+                                              debug_lib.FWD_PROGRAM_ORDER)
+        torch.cuda.synchronize()
         # same arithmetic up to fp32 re-association and the lazily moved softmax reference: within bf16 rounding of O
-        assert np.max(np.abs(og - o_simple)) <= 2.0 ** -6, D
-        assert np.max(np.abs(lg - ref["l%d" % D])) <= 1e-4, D
+        assert np.max(np.abs(og - o_to_f64(o_s))) <= 2.0 ** -6, D
+        assert np.max(np.abs(lg - l_s.cpu().numpy().astype(np.float64))) <= 1e-4, D
+
+
+def test_tiling_variants_agree_with_the_oracle(B):
+    # the tilings that attn_fwd picks by shape (D = 64: 8-wave or 4-wave workgroups) and the D = 128
+    # one-wave-per-SIMD tiling, each forced through the debug build on a shape the dispatcher would give
+    # to another one
+    import debug_lib
+    for D, causal, variant in ((64, True, debug_lib.FWD_D64_8_WAVES), (64, False, debug_lib.FWD_D64_4_WAVES),
+                               (128, True, debug_lib.FWD_D128_ONE_WAVE_PER_SIMD),
+                               (128, False, debug_lib.FWD_D128_ONE_WAVE_PER_SIMD)):
+        q, k, v = synth.make_qkv(2, 2, 530, 610, D, seed=37)
+        scale = synth.default_scale(D)
+        o, lse = debug_lib.attn_fwd_variant(to_dev(q), to_dev(k), to_dev(v), causal, scale, variant)
+        torch.cuda.synchronize()
+        orf, lrf = attn_ref(q, k, v, causal, scale)
+        assert np.max(np.abs(o_to_f64(o) - orf)) <= O_TOL, (D, causal, variant)
+        assert np.max(np.abs(lse.cpu().numpy().astype(np.float64) - lrf)) <= LSE_TOL, (D, causal, variant)
