@@ -13,9 +13,9 @@
  *     dk[j,:] = scale * sum_{i : j in J(i)} ds_ij * q[i,:]
  *     dv[j,:] =         sum_{i : j in J(i)} p_ij  * d_o[i,:]
  *
- * (the section's "five GEMMs and one exponential"; here two of the five are computed twice,
- * once per sweep, so that no atomic reduction of dq is needed and results are bitwise
- * reproducible).  All contractions run on bf16 MFMA with fp32 accumulation; p and ds are
+ * (the single-pass form of that section has five matrix products per tile pair; here two of
+ * the five are computed twice, once per sweep, so that no atomic reduction of dq is needed and
+ * results are bitwise reproducible).  All contractions run on bf16 MFMA with fp32 accumulation; p and ds are
  * rounded to bf16 (nearest even) before the products that consume them.
  */
 #ifndef MI355_ATTN_BWD_H
@@ -65,6 +65,30 @@ int attn_bwd_f16(const void *q, const void *k, const void *v, const void *o, con
                  const float *lse, void *dq, void *dk, void *dv, float *delta_ws,
                  int B, int H, int S_q, int S_kv, int D, int causal, float scale,
                  void *stream);
+
+/*
+ * attn_bwd_noalloc -- attn_bwd for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and
+ * bitwise the same results as attn_bwd (bf16), without the delta_ws argument: the workspace is a
+ * 16 MiB array inside the library, one copy per GPU the library runs on, held until the process
+ * ends.  The call allocates nothing on the device.
+ *
+ *   limit      B * H * S_q <= 2^21 rows (2 fp32 words per row); more returns ATTN_ERR_WORKSPACE
+ *              before anything is launched.  All other arguments, layouts, ownership rules and
+ *              error codes are those of attn_bwd.
+ *   set-up     the first call on a device resolves that device's copy of the array (one runtime
+ *              query, no allocation); make that first call outside a graph capture, with the
+ *              device of `stream` current.  Every call must be made with the device of `stream`
+ *              current.
+ *   sharing    every call on a GPU uses that GPU's one array.  A call overwrites the part it uses
+ *              before reading it, so nothing has to be cleared and calls may follow each other on
+ *              one stream in any mix of sizes; calls that overlap in time on the same GPU (two
+ *              streams, or two graphs replayed concurrently) race on it and give undefined results.
+ */
+int attn_bwd_noalloc(const void *q, const void *k, const void *v, const void *o, const void *d_o,
+                     const float *lse, void *dq, void *dk, void *dv,
+                     int B, int H, int S_q, int S_kv, int D, int causal, float scale,
+                     void *stream);
 
 #ifdef __cplusplus
 }

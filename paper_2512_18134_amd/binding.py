@@ -32,6 +32,8 @@ _lib.attn_bwd.restype = ctypes.c_int
 _lib.attn_bwd.argtypes = [ctypes.c_void_p] * 10 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
 _lib.attn_bwd_f16.restype = ctypes.c_int
 _lib.attn_bwd_f16.argtypes = _lib.attn_bwd.argtypes
+_lib.attn_bwd_noalloc.restype = ctypes.c_int
+_lib.attn_bwd_noalloc.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
 _lib.attn_strerror.restype = ctypes.c_char_p
 _lib.attn_strerror.argtypes = [ctypes.c_int]
 _lib.attn_version.restype = ctypes.c_int
@@ -148,6 +150,21 @@ def attn_bwd_f16_raw(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr
                                  B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
 
 
+def attn_bwd_noalloc_raw(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr, dv_ptr,
+                         B, H, S_q, S_kv, D, causal, scale, stream_ptr):
+    """The C entry point attn_bwd_noalloc with raw integer addresses; returns the attn_status."""
+    return int(_lib.attn_bwd_noalloc(q_ptr, k_ptr, v_ptr, o_ptr, do_ptr, lse_ptr, dq_ptr, dk_ptr, dv_ptr,
+                                     B, H, S_q, S_kv, D, int(bool(causal)), float(scale), stream_ptr))
+
+
+def attn_bwd_noalloc(q, k, v, o, d_o, lse, dq, dk, dv, causal=False, scale=None, stream=None):
+    """attn_bwd_noalloc on torch device tensors: attn_bwd with the library's own workspace.  The caller
+    passes every output (this wrapper allocates nothing either).  Returns (dq, dk, dv)."""
+    import torch
+    entry = lambda *a: attn_bwd_noalloc_raw(*(a[:9] + a[10:]))   # drop the workspace address
+    return _marshal_bwd(entry, torch.bfloat16, q, k, v, o, d_o, lse, dq, dk, dv, False, causal, scale, stream)
+
+
 def attn_bwd_f16(q, k, v, o, d_o, lse, dq=None, dk=None, dv=None, delta_ws=None, causal=False, scale=None,
                  stream=None):
     """attn_bwd_f16 on torch device tensors: as attn_bwd, with fp16 tensors."""
@@ -181,6 +198,9 @@ def _marshal_bwd(entry, dt, q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, causal, 
     S_kv = k.shape[2]
     if lse.dtype != torch.float32 or tuple(lse.shape) != (B, H, S_q) or not lse.is_contiguous() or not lse.is_cuda:
         raise TypeError("lse must be a contiguous fp32 GPU tensor [B,H,S_q]")
+    no_ws = delta_ws is False          # attn_bwd_noalloc: the library's own workspace, outputs from the caller
+    if no_ws and (dq is None or dk is None or dv is None):
+        raise TypeError("attn_bwd_noalloc: the caller passes dq, dk, dv")
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv
@@ -189,8 +209,8 @@ def _marshal_bwd(entry, dt, q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, causal, 
     for t, like in ((dq, q), (dk, k), (dv, v)):
         if t.dtype != dt or t.shape != like.shape or not t.is_contiguous() or not t.is_cuda:
             raise TypeError("dq, dk, dv must be contiguous GPU tensors shaped and typed like q, k, v")
-    if (delta_ws.dtype != torch.float32 or delta_ws.numel() < 2 * B * H * S_q or not delta_ws.is_contiguous()
-            or not delta_ws.is_cuda):
+    if not no_ws and (delta_ws.dtype != torch.float32 or delta_ws.numel() < 2 * B * H * S_q
+                      or not delta_ws.is_contiguous() or not delta_ws.is_cuda):
         raise TypeError("delta_ws must be a contiguous fp32 GPU tensor with at least 2*B*H*S_q elements")
     if scale is None:
         scale = 1.0 / float(D) ** 0.5
@@ -198,7 +218,7 @@ def _marshal_bwd(entry, dt, q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, causal, 
         stream = torch.cuda.current_stream(q.device)
     with torch.cuda.device(q.device):
         rc = entry(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
-                   dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), delta_ws.data_ptr(),
+                   dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), 0 if no_ws else delta_ws.data_ptr(),
                    B, H, S_q, S_kv, D, causal, scale, stream.cuda_stream)
     if rc != ATTN_OK:
         raise AttnError(rc)

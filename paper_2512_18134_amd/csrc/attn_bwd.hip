@@ -3,11 +3,19 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "attn_bwd.h"  // the C declaration (include/)
 #include "attn_bwd_asm.h"
 #include "attn_bwd_kernels.h"
 #include "attn_fwd.h"  // attn_status
 #include "attn_launch.h"
+
+// Workspace of attn_bwd_noalloc: one copy per GPU that the library runs on, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; the device address it yields (one per
+// device) is what is passed to kernels.
+#define ATTN_BWD_NOALLOC_MAX_ROWS (1 << 21)
+static __device__ __align__(256) float scratch[2 * ATTN_BWD_NOALLOC_MAX_ROWS];
 
 namespace {
 
@@ -114,6 +122,52 @@ extern "C" int attn_bwd(const void *q, const void *k, const void *v, const void 
     const int rc = validate_bwd(q, k, v, o, d_o, lse, dq, dk, dv, delta_ws, B, H, S_q, S_kv, D, scale, p);
     if (rc != ATTN_OK)
         return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return D == 64 ? launch_bwd<64>(p, B * H, causal, st, false) : launch_bwd<128>(p, B * H, causal, st, false);
+}
+
+// device address of `scratch` on the current device; resolved on the first call on that device
+static float *scratch_on_current_device()
+{
+    constexpr int kMaxDev = 64;
+    static std::mutex mu;
+    static float *ptr[kMaxDev] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *addr = nullptr;
+        if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || !addr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr[dev] = static_cast<float *>(addr);
+    }
+    return ptr[dev];
+}
+
+extern "C" int attn_bwd_noalloc(const void *q, const void *k, const void *v, const void *o, const void *d_o,
+                                const float *lse, void *dq, void *dk, void *dv, int B, int H, int S_q, int S_kv,
+                                int D, int causal, float scale, void *stream)
+{
+    // size check on the host first: the rows must fit the library's own workspace
+    if (B >= 1 && H >= 1 && S_q >= 1 && (long long)B * H * S_q > ATTN_BWD_NOALLOC_MAX_ROWS)
+        return ATTN_ERR_WORKSPACE;
+    BwdParams p;
+    float dummy_ws = 0.f;  // validate_bwd only looks at the address
+    const int rc = validate_bwd(q, k, v, o, d_o, lse, dq, dk, dv, &dummy_ws, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    float *ws = scratch_on_current_device();
+    if (!ws)
+        return ATTN_ERR_LAUNCH;
+    // every word of the workspace that the sweeps read is written by the Delta kernel of this call:
+    // nothing has to start at zero
+    p.lse2 = ws;
+    p.delta = ws + (long long)B * H * S_q;
     hipStream_t st = static_cast<hipStream_t>(stream);
     return D == 64 ? launch_bwd<64>(p, B * H, causal, st, false) : launch_bwd<128>(p, B * H, causal, st, false);
 }

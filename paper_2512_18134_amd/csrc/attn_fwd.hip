@@ -338,7 +338,8 @@ extern "C" const char *attn_strerror(int status)
     case ATTN_ERR_UNSUPPORTED:
         return "this entry point does not implement the requested combination (e.g. causal split-KV)";
     case ATTN_ERR_WORKSPACE:
-        return "the workspace is smaller than attn_fwd_splitkv_workspace_bytes() asks for";
+        return "the workspace is too small: smaller than attn_fwd_splitkv_workspace_bytes() asks for, or the shape exceeds "
+               "the built-in workspace of attn_bwd_noalloc (B*H*S_q <= 2^21)";
     }
     return "unknown attn_status";
 }

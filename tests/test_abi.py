@@ -132,6 +132,15 @@ def test_bwd_entry_validates_before_any_launch(binding):
     for s in (float("nan"), float("inf"), -1.0):
         assert f(scale=s) == b.ATTN_ERR_SCALE
     assert f(S_q=1 << 24, D=128) == b.ATTN_ERR_SHAPE
+    # the entry point with the library's own workspace: same checks, and a limit on the rows
+    def g(**kw):
+        ptrs = [kw.get(n, ok) for n in names[:-1]]
+        rest = [kw.get(n, d) for n, d in (("B", 1), ("H", 1), ("S_q", 8), ("S_kv", 8), ("D", 64), ("causal", 0),
+                                           ("scale", 0.125), ("stream", 0))]
+        return b.attn_bwd_noalloc_raw(*(ptrs + rest))
+    assert g(q=0) == b.ATTN_ERR_NULL and g(B=0) == b.ATTN_ERR_SHAPE and g(dk=ok + 8) == b.ATTN_ERR_ALIGN
+    assert g(D=256) == b.ATTN_ERR_UNSUPPORTED_D
+    assert g(S_q=(1 << 21) + 1) == b.ATTN_ERR_WORKSPACE and g(B=2, H=1 << 10, S_q=1 << 10 | 1) == b.ATTN_ERR_WORKSPACE
     # the fp16 entry: same checks, and scale > 0 only
     def h(**kw):
         ptrs = [kw.get(n, ok) for n in names]
