@@ -38,14 +38,10 @@ def generate_sources(verbose=False, out_dir=None):
     gen = os.path.join(HERE, "csrc", "gen_attn_loop.py")
     out_dir = out_dir or os.path.join(HERE, "csrc", "generated")
     os.makedirs(out_dir, exist_ok=True)
-    for d, dtype, nw in ((64, "bf16", 8), (128, "bf16", 8), (64, "f16", 8), (128, "f16", 8), (64, "bf16", 4)):
-        out = os.path.join(out_dir, "attn_loop_d%d%s%s.inc" % (d, "" if dtype == "bf16" else "_" + dtype,
-                                                               "" if nw == 8 else "_w%d" % nw))
-        _run_generator([sys.executable, gen, str(d), out, dtype, str(nw)], verbose)
-    gen2 = os.path.join(HERE, "csrc", "gen_attn_loop2.py")
-    for name, dtype in (("d128a", "bf16"), ("d256a", "bf16"), ("d256a", "f16")):
+    for name, dtype in (("d64", "bf16"), ("d64", "f16"), ("d64_w4", "bf16"), ("d128", "bf16"), ("d128", "f16"),
+                        ("d128a", "bf16"), ("d128a", "f16"), ("d256a", "bf16"), ("d256a", "f16")):
         out = os.path.join(out_dir, "attn_loop_%s%s.inc" % (name, "" if dtype == "bf16" else "_" + dtype))
-        _run_generator([sys.executable, gen2, name, out, dtype], verbose)
+        _run_generator([sys.executable, gen, name, out, dtype], verbose)
     gen3 = os.path.join(HERE, "csrc", "gen_attn_bwd_loop.py")
     for kind, d, dtype in (("kv", 128, "bf16"), ("q", 128, "bf16"), ("kv", 128, "f16"), ("q", 128, "f16"),
                            ("kv", 64, "bf16"), ("q", 64, "bf16"), ("kv", 64, "f16"), ("q", 64, "f16")):

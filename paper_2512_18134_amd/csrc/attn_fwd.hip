@@ -7,7 +7,6 @@
 
 #include "attn_fwd.h"
 #include "attn_fwd_asm.h"
-#include "attn_fwd_asm2.h"
 #include "attn_fwd_simple.h"
 #include "attn_launch.h"
 #include "attn_splitkv.h"
@@ -43,43 +42,34 @@ int launch_simple(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_simple_kernel<D, BN, NW, false>, p, BH, NW * 32, NW * 64, LDS, stream);
 }
 
-// w4: -1 = choose, 0 / 1 = 8-wave / 4-wave workgroups (D = 64 only)
-template <int D>
-int launch_asm(const Params &p, int BH, int causal, hipStream_t stream, int w4 = -1)
+// one hand-scheduled tiling: QB 32-row query blocks per wave, SB 32-key blocks per K/V tile, NW waves
+template <int D, int QB, int SB, int NW, bool F16 = false>
+int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
 {
-    constexpr int LDS = 8 * 64 * D * 2;
-    if constexpr (D == 64) {
-        // Measured: two 4-wave workgroups per CU instead of one 8-wave one change little when every
-        // workgroup streams the same number of tiles (-3 % at long S, +-2 % at short S); with a causal mask
-        // and few tiles the finer query tiles balance better (+13 % at S = 1024, +4 % at S = 4096).
-        const bool use4 = w4 >= 0 ? w4 != 0 : (causal && p.S_kv <= kW4MaxKeys);
-        if (use4) {
-            if (causal)
-                return launch(attn::attn_fwd_asm_kernel<64, true, false, false, 4>, p, BH, 128, 256, LDS, stream);
-            return launch(attn::attn_fwd_asm_kernel<64, false, false, false, 4>, p, BH, 128, 256, LDS, stream);
-        }
-    }
+    constexpr int LDS = 8 * 32 * SB * D * 2, BM = 32 * QB * NW;
     if (causal)
-        return launch(attn::attn_fwd_asm_kernel<D, true>, p, BH, 256, 512, LDS, stream);
-    return launch(attn::attn_fwd_asm_kernel<D, false>, p, BH, 256, 512, LDS, stream);
+        return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, true, F16>, p, BH, BM, NW * 64, LDS, stream);
+    return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, false, F16>, p, BH, BM, NW * 64, LDS, stream);
 }
 
-template <int D>
-int launch_asm_f16(const Params &p, int BH, int causal, hipStream_t stream)
+// D = 64.  w4: -1 = choose, 0 / 1 = 8-wave / 4-wave workgroups.
+// Measured: two 4-wave workgroups per CU instead of one 8-wave one change little when every workgroup
+// streams the same number of tiles (-3 % at long S, +-2 % at short S); with a causal mask and few tiles
+// the finer query tiles balance better (+13 % at S = 1024, +4 % at S = 4096).
+int launch_d64(const Params &p, int BH, int causal, hipStream_t stream, int w4 = -1)
 {
-    constexpr int LDS = 8 * 64 * D * 2;
-    if (causal)
-        return launch(attn::attn_fwd_asm_kernel<D, true, true>, p, BH, 256, 512, LDS, stream);
-    return launch(attn::attn_fwd_asm_kernel<D, false, true>, p, BH, 256, 512, LDS, stream);
+    const bool use4 = w4 >= 0 ? w4 != 0 : (causal && p.S_kv <= kW4MaxKeys);
+    return use4 ? launch_asm<64, 1, 2, 4>(p, BH, causal, stream) : launch_asm<64, 1, 2, 8>(p, BH, causal, stream);
 }
 
-template <int D, int QB, bool F16 = false>
-int launch_asm2(const Params &p, int BH, int causal, hipStream_t stream)
+// D = 128.  wide: -1 = choose, 0 = 8 waves x 32 rows (two waves per SIMD), 1 = 4 waves x 64 rows (one wave
+// per SIMD, half the LDS operand reads per MFMA).
+template <bool F16>
+int launch_d128(const Params &p, int BH, int causal, hipStream_t stream, int wide = -1)
 {
-    constexpr int LDS = 8 * 32 * D * 2;
-    if (causal)
-        return launch(attn::attn_fwd_asm2_kernel<D, QB, true, F16>, p, BH, 128 * QB, 256, LDS, stream);
-    return launch(attn::attn_fwd_asm2_kernel<D, QB, false, F16>, p, BH, 128 * QB, 256, LDS, stream);
+    const bool use_wide = wide >= 0 ? wide != 0 : true;
+    return use_wide ? launch_asm<128, 2, 1, 4, F16>(p, BH, causal, stream)
+                    : launch_asm<128, 1, 2, 8, F16>(p, BH, causal, stream);
 }
 
 // the generic kernel: any scale, heads of any size, program order
@@ -104,11 +94,11 @@ int dispatch_fwd(const Params &p, int BH, int D, int causal, hipStream_t st)
         return launch_generic(p, BH, D, causal, st);
     switch (D) {
     case 64:
-        return launch_asm<64>(p, BH, causal, st);
+        return launch_d64(p, BH, causal, st);
     case 128:
-        return launch_asm<128>(p, BH, causal, st);
+        return launch_d128<false>(p, BH, causal, st);
     default:
-        return launch_asm2<256, 1>(p, BH, causal, st);
+        return launch_asm<256, 1, 1, 4>(p, BH, causal, st);
     }
 }
 
@@ -178,7 +168,7 @@ static int launch_splitkv(Params &p, int BH, int n_eff, void *o, float *lse, hip
         return ATTN_ERR_SHAPE;
     p.total_wg = (int)total;
     const int lds = 8 * 64 * D * 2;
-    auto kern = attn::attn_fwd_asm_kernel<D, false, F16, true>;
+    auto kern = attn::attn_fwd_asm_kernel<D, 1, 2, 8, false, F16, true>;
     if (!allow_lds(reinterpret_cast<const void *>(kern), lds))
         return ATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(512), lds, st, p);
@@ -219,8 +209,8 @@ static int splitkv_entry(const void *q, const void *k, const void *v, void *o, f
     const int n_eff = split_plan(S_kv, n_split, p.split_len);
     if (n_eff == 1) {  // one range: the plain kernel writes o and lse itself
         if (F16)
-            return D == 64 ? launch_asm_f16<64>(p, B * H, 0, st) : launch_asm_f16<128>(p, B * H, 0, st);
-        return D == 64 ? launch_asm<64>(p, B * H, 0, st) : launch_asm<128>(p, B * H, 0, st);
+            return D == 64 ? launch_asm<64, 1, 2, 8, true>(p, B * H, 0, st) : launch_d128<true>(p, B * H, 0, st);
+        return D == 64 ? launch_d64(p, B * H, 0, st) : launch_d128<false>(p, B * H, 0, st);
     }
     const long long n_rows = (long long)B * H * S_q;
     p.n_split = n_eff;
@@ -260,8 +250,8 @@ extern "C" int attn_fwd_f16(const void *q, const void *k, const void *v, void *o
         return ATTN_ERR_SCALE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (D == 256)
-        return launch_asm2<256, 1, true>(p, B * H, causal, st);
-    return D == 64 ? launch_asm_f16<64>(p, B * H, causal, st) : launch_asm_f16<128>(p, B * H, causal, st);
+        return launch_asm<256, 1, 1, 4, true>(p, B * H, causal, st);
+    return D == 64 ? launch_asm<64, 1, 2, 8, true>(p, B * H, causal, st) : launch_d128<true>(p, B * H, causal, st);
 }
 
 extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
@@ -277,8 +267,9 @@ extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, fl
 #ifdef ATTN_DEBUG_ENTRY_POINTS
 // Test-only entry point of the debug build of the library (libmi355attn_debug.so): attn_fwd with the
 // kernel chosen by the caller.  variant 0: as attn_fwd; 1: the generic program-order kernel;
-// 2: D = 128 on the one-wave-per-SIMD tiling (64 query rows per wave); 3 / 4: D = 64 with 8-wave /
-// 4-wave workgroups.  A variant that does not apply to the arguments returns ATTN_ERR_UNSUPPORTED.
+// 2 / 5: D = 128 on the one-wave-per-SIMD tiling (4 waves x 64 query rows) / on the two-waves-per-SIMD
+// tiling (8 waves x 32 rows); 3 / 4: D = 64 with 8-wave / 4-wave workgroups.  A variant that does not
+// apply to the arguments returns ATTN_ERR_UNSUPPORTED.
 extern "C" int attn_fwd_variant(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H,
                                 int S_q, int S_kv, int D, int causal, float scale, void *stream, int variant)
 {
@@ -294,10 +285,12 @@ extern "C" int attn_fwd_variant(const void *q, const void *k, const void *v, voi
     case 1:
         return launch_generic(p, B * H, D, causal, st);
     case 2:
-        return D == 128 && asm_ok ? launch_asm2<128, 2>(p, B * H, causal, st) : ATTN_ERR_UNSUPPORTED;
+        return D == 128 && asm_ok ? launch_d128<false>(p, B * H, causal, st, 1) : ATTN_ERR_UNSUPPORTED;
+    case 5:
+        return D == 128 && asm_ok ? launch_d128<false>(p, B * H, causal, st, 0) : ATTN_ERR_UNSUPPORTED;
     case 3:
     case 4:
-        return D == 64 && asm_ok ? launch_asm<64>(p, B * H, causal, st, variant - 3) : ATTN_ERR_UNSUPPORTED;
+        return D == 64 && asm_ok ? launch_d64(p, B * H, causal, st, variant - 3) : ATTN_ERR_UNSUPPORTED;
     }
     return ATTN_ERR_UNSUPPORTED;
 }

@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Emit the hand-scheduled main loop of the gfx950 attention-forward kernel.
+"""Emit the hand-scheduled main loop of the gfx950 attention-forward kernels.
 
 The loop is the paper's Fig. 1a, modulo-scheduled by hand for CDNA4 (Section 3.1
 vocabulary: initiation interval I = one K/V tile = NM MFMA slots per wave,
@@ -9,36 +9,48 @@ in-order instruction stream per wave,
     slot i:  [s_waitcnt for the operand of MFMA i]
              MFMA i            -- first half of P(j-1) V(j-1), then K(j+1) Q^T,
                                   then the second half of P(j-1) V(j-1)
-             LDS reads for MFMA i+PFD (K fragment: ds_read_b128, V^T fragment:
+             LDS reads for a later MFMA (K fragment: ds_read_b128, V^T fragment:
                                   2 x ds_read_b64_tr_b16), a ring of NF buffers
-             ~VPS VALU/transcendental ops of softmax(S(j)): fma -> exp2 -> row-sum
-                                  add -> bf16 pack, software pipelined over element
-                                  pairs (no row maximum on this path, see below)
+             this slot's share of softmax(S(j)): fma -> exp2 -> row-sum add ->
+                                  16-bit pack, software pipelined over element pairs
 
-so that the matrix pipe (32 cycles per MFMA) and the VALU run side by side; the
-same stream runs on two waves per SIMD, which fills the remaining bubbles.
+so that the matrix pipe (32 cycles per MFMA) and the VALU run side by side.
 K/V tiles arrive by direct global->LDS loads into 4-stage rings, two tiles
 ahead, with one workgroup barrier per tile.
+
+Tilings (CONFIGS): a wave owns QB blocks of 32 query rows; a K/V tile holds SB
+blocks of 32 keys; a fragment read from LDS feeds QB MFMAs.
+  * two waves per SIMD (8 waves x 32 rows): all 256 VGPRs of a wave are assigned
+    here, O and Q included; the hardware arbiter interleaves the two streams;
+  * one wave per SIMD (4 waves x 64 rows at D = 128, 4 x 32 at D = 256): the wave
+    owns the SIMD's 512 registers, O and Q sit in AGPRs (the MFMA reads and writes
+    them directly), everything the VALU touches in VGPRs.  Half the LDS operand
+    reads per MFMA at D = 128; the stream has to keep the matrix pipe fed alone,
+    so the instruction count per MFMA is what bounds it (see asm_emit.spread).
 
 Online softmax without a per-tile row maximum.  P = exp2(c s - c m_ref) is
 taken against the reference m_ref the row already has; floating point is scale
 invariant, so a reference that lags the true maximum costs no accuracy as long
-as nothing overflows.  The only per-tile test is therefore on the tile's row
-sum (which is needed anyway): if it is not below 2^8 (an element has grown
-too large, has overflowed, or m_ref is still -inf in the first tile) the wave
-leaves the interleaved stream for an out-of-line pass that finds the exact row
-maximum of the tile, moves m_ref there, scales the running sum (and, deferred
-to the end of the iteration, the accumulator) by alpha = exp2(c (m_old - m_new))
-and recomputes the tile's P from its scores, which the fast path leaves intact
-(the exponent arguments go to temporaries).  On N(0,1) inputs this pass runs
-once per workgroup; it replaces 29 of the 140 VALU operations per tile.
+as nothing overflows.  The only per-tile test is on the tile's row sum (needed
+anyway): if it is not below 2^8 (an element has grown large, has overflowed, or
+m_ref is still -inf in the first tile) the wave leaves the interleaved stream
+for an out-of-line pass that finds the exact row maximum of the tile, moves
+m_ref there, scales the running sum and the accumulator by
+alpha = exp2(c (m_old - m_new)) and recomputes the tile's P from its scores,
+which the fast path leaves intact (the exponent arguments go to temporaries).
+On N(0,1) inputs this pass runs once per workgroup.
 
-The compiler cannot be made to hold this schedule inside 256 VGPRs (it spills),
-so registers are assigned here and the loop is emitted as ONE inline-asm
-statement with operands pinned to physical registers.  Everything around the
-loop (addressing, Q load, S(0), normalisation, stores) stays in HIP C++.
+Rare events share one test per iteration: j >= s_special (loop exit, tiles that
+need a mask, tiles whose loads reach past S_kv) branches out of line and comes
+back with SCC set, which the two load slots test again.
 
-Hazards handled by construction (the assembler inserts no wait states):
+The compiler cannot be made to hold this schedule (it spills), so registers are
+assigned here and the loop is emitted as ONE inline-asm statement with operands
+pinned to physical registers.  Everything around the loop (addressing, Q load,
+S(0), normalisation, stores) stays in HIP C++ (attn_fwd_asm.h).
+
+Hazards handled by construction (the assembler inserts no wait states; the rules
+are re-checked on the emitted text by asm_emit.check_stream in the tests):
   * MFMA result -> VALU read needs 11 wait states for an 8-pass MFMA: the
     K Q^T MFMAs sit in the middle of the iteration, S is first read in the next;
     explicit s_nop before the accumulator rescale and at loop exit.
@@ -47,118 +59,140 @@ Hazards handled by construction (the assembler inserts no wait states):
   * LDS reads return in order: every s_waitcnt lgkmcnt(N) is computed by
     replaying the instruction stream (including the reads prefetched for the
     next iteration).
+  * scalar write of m0 -> direct load needs 1 wait state: an s_nop goes between
+    them.
 
-usage: gen_attn_loop.py <D> <out.inc> [bf16|f16] [waves per workgroup: 8|4] [--pfd N] [--drop part,part]
-(--pfd and --drop exist for timing experiments; a library build passes neither)
+usage: gen_attn_loop.py <config> <out.inc> [bf16|f16] [--pfd N] [--nf N] [--drop part,part]
+(--pfd, --nf and --drop exist for timing experiments; a library build passes none)
 """
+import os
 import struct
 import sys
 
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from asm_emit import Emitter, spread  # noqa: E402
 
-class Gen:
-    def __init__(self, D, NF=4, PFD=3, dtype="bf16", NW=8, drop=()):
-        assert D in (64, 128) and dtype in ("bf16", "f16") and NW in (4, 8)
-        self.NW = NW                      # waves per workgroup: every wave loads 1/NW of each K/V tile
-        self.D = D
-        self.dtype = dtype
+CONFIGS = {
+    # D: head dimension; QB: 32-row query blocks per wave; SB: 32-key blocks per K/V tile; NW: waves per
+    # workgroup; AG: O and Q in AGPRs (one wave per SIMD); NACC: K Q^T accumulators per score block
+    "d64":    dict(D=64,  QB=1, SB=2, NW=8, AG=False, NACC=1),
+    "d64_w4": dict(D=64,  QB=1, SB=2, NW=4, AG=False, NACC=1),
+    "d128":   dict(D=128, QB=1, SB=2, NW=8, AG=False, NACC=1),
+    "d128a":  dict(D=128, QB=2, SB=1, NW=4, AG=True,  NACC=1),
+    "d256a":  dict(D=256, QB=1, SB=1, NW=4, AG=True,  NACC=2),
+}
+
+
+class Gen(Emitter):
+    def __init__(self, name, dtype="bf16", NF=4, PFD=3, drop=()):
+        Emitter.__init__(self)
+        cfg = CONFIGS[name]
+        assert dtype in ("bf16", "f16")
+        self.name, self.dtype = name, dtype
         # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
         self.mfma = "v_mfma_f32_32x32x16_" + dtype
         self.cvt = "v_cvt_pk_%s_f32" % dtype
-        self.KS = D // 16
-        self.DB = D // 32
+        D, QB, SB, NW = cfg["D"], cfg["QB"], cfg["SB"], cfg["NW"]
+        self.D, self.QB, self.SB, self.NW, self.AG, self.NACC = D, QB, SB, NW, cfg["AG"], cfg["NACC"]
+        self.BN = 32 * SB
+        self.KS = D // 16                         # k-steps of K Q^T
+        self.DB = D // 32                         # 32-wide blocks of the head dimension
         self.ROWB = 2 * D
-        self.TB = 64 * self.ROWB
-        self.NLD = self.TB // (NW * 1024)
-        self.NSTG = 4
+        self.TB = self.BN * self.ROWB             # bytes of one K (or V) tile
+        self.NLD = self.TB // (NW * 1024)         # direct loads per wave, tile and tensor
+        assert self.NLD >= 1 and self.TB % (NW * 1024) == 0
         self.NF, self.PFD = NF, PFD
-        self.NPV = 4 * self.DB
-        self.NQK = 2 * self.KS
-        self.NM = self.NPV + self.NQK
-        assert self.NM % NF == 0 and PFD < NF
-        # ---- VGPR map
-        r = 0
-        def take(n):
-            nonlocal r
-            b = r
-            r += n
+        self.NPVG = 2 * SB * self.DB              # fragment groups of P V
+        self.NQKG = self.KS * SB                  # fragment groups of K Q^T
+        self.NG = self.NPVG + self.NQKG
+        self.NM = self.NG * QB                    # MFMA slots per iteration
+        assert self.NG % NF == 0 and PFD < NF
+        # timing experiments only (results are wrong with any of these set): parts of the loop to leave out
+        self.exp = set(drop)
+        # ---- register map
+        v = [0]
+        a = [0]
+        def take(n, agpr=False):
+            c = a if agpr else v
+            b = c[0]
+            c[0] += n
             return b
-        self.O = take(16 * self.DB)
-        self.Q = take(4 * self.KS)
-        self.SA = take(32)
-        self.SB = take(32)
-        self.PA = take(16)
-        self.PB = take(16)
+        self.O = take(16 * QB * self.DB, self.AG)            # O[qb][db]
+        self.Q = take(4 * QB * self.KS, self.AG)             # Q[qb][ks]
+        self.SA = take(16 * QB * SB * self.NACC)             # S double buffer: [qb][sb][acc]
+        self.SBUF = take(16 * QB * SB * self.NACC)
+        self.PA = take(8 * QB * SB)                          # P double buffer: [qb][pair]
+        self.PB = take(8 * QB * SB)
         self.FR = take(4 * NF)
         self.KOFF = take(self.KS)
         self.VOFF = take(2 * self.DB)
         self.DVOFF = take(self.NLD)
         self.DROW = take(self.NLD)
         self.DCH = take(self.NLD)
-        self.MREF = take(1)
-        self.MRC = take(1)
-        self.L = take(1)                  # running row sum (this lane's half of the keys)
-        self.TLA = take(1)                # row sum of the current tile, two partial sums
-        self.TLB = take(1)
+        self.MREF = take(QB)
+        self.MRC = take(QB)
+        self.L = take(QB)                 # running row sums (this lane's half of the keys)
+        self.TLA = take(QB)               # row sums of the current tile, two partial sums each
+        self.TLB = take(QB)
         self.TP = take(6)                 # exponent / exp temporaries of three element pairs in flight
-        self.ALPHA = take(1)
-        self.THRB = take(1)
-        self.MX0 = take(1)
-        self.MX1 = take(1)
-        self.T = take(1)
-        self.TMP2 = take(1)
-        self.DD = take(1)
+        self.ALPHA = take(QB)
+        self.THRB = take(QB)
+        self.THR = take(QB)
+        self.T = take(QB)
+        self.TMP2 = take(QB)
+        self.DD = take(QB)
+        self.MX = take(2 * QB)
+        self.TS = take(1) if QB == 2 else None   # sum of the tile row sums of the two query blocks
         self.NEGINF = take(1)
-        self.THR = take(1)
-        self.DT = take(2 * self.NLD)  # address temporaries of the ragged-tile loads
-        self.NV = r
-        assert r <= 256, r
+        self.DT = take(2 * self.NLD)      # address temporaries of the ragged-tile loads
+        self.AT = take(4) if self.AG else None   # temporaries of the accumulator rescale
+        self.NV, self.NA = v[0], a[0]
+        assert self.NV <= 256 and self.NA <= 256, (self.NV, self.NA)
         # ---- SGPR map (inputs pinned by the asm constraints, the rest clobbered)
         self.s_kbase, self.s_vbase = 32, 34
         self.s_c, self.s_ntiles, self.s_jmask, self.s_tfull, self.s_skvm1 = 36, 37, 38, 39, 40
         self.s_ldsk, self.s_ldsv = 41, 42
-        self.s_j, self.s_resc, self.s_tau = 43, 44, 45
+        self.s_j, self.s_special, self.s_tau = 43, 44, 45
         self.s_kptr, self.s_vptr = 46, 48
-        self.s_tk, self.s_tv = 50, 51
-        self.s_t0 = 52            # s[52:53] scratch pair
-        self.s_t2 = 54
-        self.s_m0 = 55            # m0 of the surrounding code (reserved register: saved and restored here)
-        self.lines = []
-        # timing experiments only (results are wrong with any of these set): parts of the loop to leave out
-        self.exp = set(drop)
+        self.s_t2 = 50
+        self.s_m0 = 51            # m0 of the surrounding code (reserved register: saved and restored here)
+        self.s_lk = 52            # LDS addresses of this wave's K loads, [stage][i]
+        self.s_lv = self.s_lk + 4 * self.NLD
+        self.s_last = self.s_lv + 4 * self.NLD - 1
+        assert self.s_last < 100
+
+    # ------------------------------------------------------------------ helpers
+    def acc(self, base, n):
+        return self.ar(base, n) if self.AG else self.vr(base, n)
+
+    def s_reg(self, S, qb, sb, acc=0, r=0):
+        return S + ((qb * self.SB + sb) * self.NACC + acc) * 16 + r
+
+    def bufs(self, b):
+        """(S_cur, S_nxt, P_prev, P_new) of body b."""
+        S = (self.SA, self.SBUF) if b % 2 == 0 else (self.SBUF, self.SA)
+        P = (self.PA, self.PB) if b % 2 == 0 else (self.PB, self.PA)
+        return S[0], S[1], P[0], P[1]
 
     def tau_bits(self):
         """Bound on a lane's row sum over one tile, as fp32 bits: 2^8, so every P of a tile that passes is
         below 2^8 (inside fp16's range too).  The bound could be far larger without overflow (bf16 has
         fp32's exponent range), but a small one keeps one-hot rows exact: a key that outgrows the reference
         by more than a few bits moves the reference onto itself, its P is then exactly 1 and O is exactly
-        its V row; with a lagging reference its P = 2^x would be rounded to bf16 (2^-9 relative)."""
+        its V row; with a lagging reference its P = 2^x would be rounded to 16 bits (2^-9 relative)."""
         return struct.unpack("<I", struct.pack("<f", 2.0 ** 8))[0]
 
-    # ------------------------------------------------------------------ helpers
-    def e(self, s):
-        self.lines.append(s)
-
-    def lab(self, name):
-        return "%s%%=" % name   # unique per expansion of the asm statement
-
-    def vr(self, base, n=1):
-        return "v%d" % base if n == 1 else "v[%d:%d]" % (base, base + n - 1)
-
-    def sr(self, base, n=1):
-        return "s%d" % base if n == 1 else "s[%d:%d]" % (base, base + n - 1)
-
     # ------------------------------------------------------------ MFMA programs
-    def mfma_list(self):
-        """[(kind, a, b)] in issue order: ('pv', kc, db) and ('qk', ks, sb)."""
-        DB, KS = self.DB, self.KS
-        pv = [("pv", kc, db) for kc in range(4) for db in range(DB)]
-        qk = [("qk", ks, sb) for ks in range(KS) for sb in range(2)]
-        return pv[:2 * DB] + qk + pv[2 * DB:]
+    def groups(self):
+        """Fragment groups in issue order: ('pv', kc, db) and ('qk', ks, sb); each feeds QB MFMAs."""
+        pv = [("pv", kc, db) for kc in range(2 * self.SB) for db in range(self.DB)]
+        qk = [("qk", ks, sb) for ks in range(self.KS) for sb in range(self.SB)]
+        return pv[:self.NPVG // 2] + qk + pv[self.NPVG // 2:]
 
-    def frag_loads(self, op, buf, kst, vst):
-        """LDS reads that bring the A operand of `op` into fragment buffer `buf`."""
+    def frag_loads(self, grp, buf, kst, vst):
+        """LDS reads that bring the A operand of group `grp` into fragment buffer `buf`."""
         f = self.FR + 4 * buf
-        kind, a, b = op
+        kind, a, b = grp
         if "nolds" in self.exp:
             return []
         if kind == "pv":
@@ -172,303 +206,348 @@ class Gen:
         assert off < 65536
         return ["ds_read_b128 %s, %s offset:%d" % (self.vr(f, 4), self.vr(self.KOFF + ks), off)]
 
-    def mfma_text(self, op, buf, P_prev, S_nxt):
+    def mfma_texts(self, grp, buf, P_prev, S_nxt):
         f = self.vr(self.FR + 4 * buf, 4)
-        kind, a, b = op
-        if kind == "pv":
-            kc, db = a, b
-            o = self.vr(self.O + 16 * db, 16)
-            return "%s %s, %s, %s, %s" % (self.mfma, o, f, self.vr(P_prev + 4 * kc, 4), o)
-        ks, sb = a, b
-        s = self.vr(S_nxt + 16 * sb, 16)
-        return "%s %s, %s, %s, %s" % (self.mfma, s, f, self.vr(self.Q + 4 * ks, 4), "0" if ks == 0 else s)
+        kind, a, b = grp
+        out = []
+        for qb in range(self.QB):
+            if kind == "pv":
+                kc, db = a, b
+                o = self.acc(self.O + 16 * (qb * self.DB + db), 16)
+                out.append("%s %s, %s, %s, %s" % (self.mfma, o, f, self.vr(P_prev + qb * 8 * self.SB + 4 * kc, 4), o))
+            else:
+                ks, sb = a, b
+                s = self.vr(self.s_reg(S_nxt, qb, sb, ks % self.NACC), 16)
+                q = self.acc(self.Q + 4 * (qb * self.KS + ks), 4)
+                out.append("%s %s, %s, %s, %s" % (self.mfma, s, f, q, "0" if ks < self.NACC else s))
+        return out
 
     # ---------------------------------------------------------- softmax programs
-    def max_ops(self, S_cur):
-        """Row max of the lane's 32 scores into T, two interleaved max3 chains."""
-        ops = []
-        if "nomax" in self.exp:
-            return []
-        ch = [[], []]
-        for c, mx in enumerate((self.MX0, self.MX1)):
-            s = [S_cur + 16 * c + i for i in range(16)]
-            ch[c].append("v_max3_f32 v%d, v%d, v%d, v%d" % (mx, s[0], s[1], s[2]))
-            for i in range(3, 15, 2):
-                ch[c].append("v_max3_f32 v%d, v%d, v%d, v%d" % (mx, mx, s[i], s[i + 1]))
-            ch[c].append("v_max_f32 v%d, v%d, v%d" % (mx, mx, s[15]))
-        for a, b in zip(ch[0], ch[1]):
-            ops += [a, b]
-        ops.append("v_max_f32 v%d, v%d, v%d" % (self.T, self.MX0, self.MX1))
-        return ops
+    def pairs(self):
+        return [(qb, k) for qb in range(self.QB) for k in range(8 * self.SB)]
 
-    def pairmax_ops(self):
-        """Lane-pair max (the two lanes that hold one query's keys) and the new reference maximum into T."""
-        T, TMP2 = self.T, self.TMP2
-        return [
-            "v_mov_b32 v%d, v%d" % (TMP2, T),
-            "s_nop 1",
-            "v_permlane32_swap_b32 v%d, v%d" % (T, TMP2),   # T = {lo,lo}, TMP2 = {hi,hi}
-            "s_nop 1",
-            "v_max_f32 v%d, v%d, v%d" % (T, T, TMP2),
-            "v_max_f32 v%d, v%d, v%d" % (T, T, self.MREF),  # m_new
-        ]
+    def pair_regs(self, S_cur, p):
+        qb, k = p
+        r = self.s_reg(S_cur, qb, k // 8, 0, 2 * (k % 8))
+        return r, r + 1
 
     def pair_ops(self, S_cur, P_new):
-        """fma -> exp2 -> row-sum add -> bf16 pack over the 16 element pairs, software pipelined three deep.
+        """fma -> exp2 -> row-sum add -> 16-bit pack over the element pairs, software pipelined three deep.
         The exponent arguments go to the temporaries TP: S_cur stays intact for the out-of-line pass."""
-        ops = []
-        def tp(k, i):
-            return self.TP + 2 * (k % 3) + i
-        def F(k):
-            return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (tp(k, i), S_cur + 2 * k + i, self.s_c, self.MRC) for i in (0, 1)]
-        def E(k):
-            return ["v_exp_f32 v%d, v%d" % (tp(k, i), tp(k, i)) for i in (0, 1)]
-        def A(k):
-            if k == 0:   # the first pair starts the tile's two partial sums
-                acc = ["v_mov_b32 v%d, v%d" % (self.TLA, tp(k, 0)), "v_mov_b32 v%d, v%d" % (self.TLB, tp(k, 1))]
+        pairs = self.pairs()
+        def tp(t, i):
+            return self.TP + 2 * (t % 3) + i
+        def F(t):
+            qb = pairs[t][0]
+            return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (tp(t, i), x, self.s_c, self.MRC + qb)
+                    for i, x in enumerate(self.pair_regs(S_cur, pairs[t]))]
+        def E(t):
+            return ["v_exp_f32 v%d, v%d" % (tp(t, i), tp(t, i)) for i in (0, 1)]
+        def A(t):
+            qb, k = pairs[t]
+            if k == 0:   # the first pair of a query block starts its two partial sums
+                acc = ["v_mov_b32 v%d, v%d" % (self.TLA + qb, tp(t, 0)), "v_mov_b32 v%d, v%d" % (self.TLB + qb, tp(t, 1))]
             else:
-                acc = ["v_add_f32 v%d, v%d, v%d" % (self.TLA, self.TLA, tp(k, 0)),
-                       "v_add_f32 v%d, v%d, v%d" % (self.TLB, self.TLB, tp(k, 1))]
-            return acc + ["%s v%d, v%d, v%d" % (self.cvt, P_new + k, tp(k, 0), tp(k, 1))]
+                acc = ["v_add_f32 v%d, v%d, v%d" % (self.TLA + qb, self.TLA + qb, tp(t, 0)),
+                       "v_add_f32 v%d, v%d, v%d" % (self.TLB + qb, self.TLB + qb, tp(t, 1))]
+            return acc + ["%s v%d, v%d, v%d" % (self.cvt, P_new + qb * 8 * self.SB + k, tp(t, 0), tp(t, 1))]
         if "novalu" in self.exp:
             return []
-        for t in range(16 + 2):
-            if t < 16:
+        ops = []
+        n = len(pairs)
+        for t in range(n + 2):
+            if t < n:
                 ops += F(t)
-            if 0 <= t - 1 < 16:
+            if 0 <= t - 1 < n:
                 ops += E(t - 1)
-            if 0 <= t - 2 < 16:
+            if 0 <= t - 2 < n:
                 ops += A(t - 2)
-        ops.append("v_add_f32 v%d, v%d, v%d" % (self.TLA, self.TLA, self.TLB))
+        for qb in range(self.QB):
+            ops.append("v_add_f32 v%d, v%d, v%d" % (self.TLA + qb, self.TLA + qb, self.TLB + qb))
+        if self.QB == 2:   # the sum of two positive sums is below the bound only if both are; inf / NaN carry over
+            ops.append("v_add_f32 v%d, v%d, v%d" % (self.TS, self.TLA, self.TLA + 1))
         return ops
 
     def check_ops(self, b):
-        """Tile row sum below the bound?  Otherwise (too large, inf or NaN) take the out-of-line pass."""
-        t0 = self.sr(self.s_t0, 2)
+        """Tile row sums below the bound?  Otherwise (too large, inf or NaN) take the out-of-line pass."""
         if "novalu" in self.exp:
             return []
-        return [
-            "v_cmp_ngt_f32 %s, s%d, v%d" % (t0, self.s_tau, self.TLA),   # not (bound > sum)
-            "s_cmp_lg_u64 %s, 0" % t0,
-            "s_cbranch_scc1 %s" % self.lab("SLOW%d_" % b),
-            "%s:" % self.lab("SLOWRET%d_" % b),
-            "v_add_f32 v%d, v%d, v%d" % (self.L, self.L, self.TLA),
-        ]
+        ts = self.TS if self.QB == 2 else self.TLA
+        ops = ["v_cmp_ngt_f32 vcc, s%d, v%d" % (self.s_tau, ts),     # not (bound > sum)
+               "s_cbranch_vccnz %s" % self.lab("SLOW%d_" % b),
+               "%s:" % self.lab("SLOWRET%d_" % b)]
+        if "sgprcheck" in self.exp:
+            ops = ["v_cmp_ngt_f32 s[96:97], s%d, v%d" % (self.s_tau, ts), "s_cmp_lg_u64 s[96:97], 0",
+                   "s_cbranch_scc1 %s" % self.lab("SLOW%d_" % b), "%s:" % self.lab("SLOWRET%d_" % b)]
+        for qb in range(self.QB):
+            ops.append("v_add_f32 v%d, v%d, v%d" % (self.L + qb, self.L + qb, self.TLA + qb))
+        return ops
+
+    def combine_ops(self, S_nxt):
+        """Sum the even / odd k-step accumulators of K(j+1) Q^T (NACC == 2)."""
+        ops = []
+        if self.NACC == 2:
+            for qb in range(self.QB):
+                for sb in range(self.SB):
+                    for r in range(16):
+                        a0, a1 = self.s_reg(S_nxt, qb, sb, 0, r), self.s_reg(S_nxt, qb, sb, 1, r)
+                        ops.append("v_add_f32 v%d, v%d, v%d" % (a0, a0, a1))
+        return ops
+
+    def max_ops(self, S_cur):
+        """Row maxima of the lane's scores into T[qb]: two interleaved max3 chains per query block."""
+        chains = []
+        for qb in range(self.QB):
+            els = [self.s_reg(S_cur, qb, sb, 0, r) for sb in range(self.SB) for r in range(16)]
+            half = len(els) // 2
+            for c in range(2):
+                mx, s = self.MX + 2 * qb + c, els[c * half:(c + 1) * half]
+                ch = ["v_max3_f32 v%d, v%d, v%d, v%d" % (mx, s[0], s[1], s[2])]
+                i = 3
+                while i + 1 < len(s):
+                    ch.append("v_max3_f32 v%d, v%d, v%d, v%d" % (mx, mx, s[i], s[i + 1]))
+                    i += 2
+                if i < len(s):
+                    ch.append("v_max_f32 v%d, v%d, v%d" % (mx, mx, s[i]))
+                chains.append(ch)
+        ops = []
+        for step in range(len(chains[0])):
+            for ch in chains:
+                ops.append(ch[step])
+        for qb in range(self.QB):
+            ops.append("v_max_f32 v%d, v%d, v%d" % (self.T + qb, self.MX + 2 * qb, self.MX + 2 * qb + 1))
+        return ops
+
+    def pairmax_ops(self):
+        """Max over the two lanes that hold one query's keys, and the new reference maximum, into T[qb]."""
+        seqs = []
+        for qb in range(self.QB):
+            T, TMP2 = self.T + qb, self.TMP2 + qb
+            seqs.append([
+                "v_mov_b32 v%d, v%d" % (TMP2, T),
+                "s_nop 1",
+                "v_permlane32_swap_b32 v%d, v%d" % (T, TMP2),   # T = {lo,lo}, TMP2 = {hi,hi}
+                "s_nop 1",
+                "v_max_f32 v%d, v%d, v%d" % (T, T, TMP2),
+                "v_max_f32 v%d, v%d, v%d" % (T, T, self.MREF + qb),  # m_new
+            ])
+        return [seqs[qb][i] for i in range(len(seqs[0])) for qb in range(self.QB)]
+
+    def rescale_o_ops(self):
+        """O *= alpha per query block (accumulators in VGPRs: in place; in AGPRs: read, scale, write back)."""
+        ops = []
+        for qb in range(self.QB):
+            regs = [self.O + 16 * (qb * self.DB + db) + r for db in range(self.DB) for r in range(16)]
+            if not self.AG:
+                ops += ["v_mul_f32 v%d, v%d, v%d" % (x, self.ALPHA + qb, x) for x in regs]
+                continue
+            for i in range(0, len(regs), 4):
+                ops += ["v_accvgpr_read_b32 v%d, a%d" % (self.AT + t, regs[i + t]) for t in range(4)]
+                ops.append("s_nop 1")
+                ops += ["v_mul_f32 v%d, v%d, v%d" % (self.AT + t, self.ALPHA + qb, self.AT + t) for t in range(4)]
+                ops.append("s_nop 1")
+                ops += ["v_accvgpr_write_b32 a%d, v%d" % (regs[i + t], self.AT + t) for t in range(4)]
+        return ops
 
     # ------------------------------------------------------------------- DMA
     def dma_fast(self, which, stage):
-        """Issue one K or V tile: NLD direct loads, scalar base already points at the tile."""
-        lds = self.s_ldsk if which == "k" else self.s_ldsv
+        """One K or V tile: NLD x (m0 <- LDS address, s_nop, direct load); the scalar base already points at
+        the tile.  The wait state between the m0 write and the load has to be an s_nop: with a VALU
+        instruction of the softmax program in its place that instruction's result came out wrong on the
+        MI355X (measured; every other use of the slot stayed correct)."""
+        tab = self.s_lk if which == "k" else self.s_lv
         ptr = self.s_kptr if which == "k" else self.s_vptr
         out = []
+        if "nodma" in self.exp:
+            return out
         for i in range(self.NLD):
-            if "nodma" in self.exp:
-                out.append([])
-                continue
-            out.append(["s_add_u32 m0, s%d, %d" % (lds, stage * self.TB + i * self.NW * 1024),
-                        "s_nop 0",
-                        "global_load_lds_dwordx4 v%d, %s" % (self.DVOFF + i, self.sr(ptr, 2))])
+            out += ["s_mov_b32 m0, s%d" % (tab + stage * self.NLD + i), "s_nop 0",
+                    "global_load_lds_dwordx4 v%d, %s" % (self.DVOFF + i, self.sr(ptr, 2))]
         return out
 
-    def dma_slow(self, which, stage, label, ret):
-        """Ragged / past-the-end tile: clamp the row index, read through the head's base pointer."""
-        lds = self.s_ldsk if which == "k" else self.s_ldsv
+    def dma_slow(self, which, stage, ahead):
+        """Ragged / past-the-end tile j + ahead: clamp the row index, read through the head's base pointer."""
+        tab = self.s_lk if which == "k" else self.s_lv
         base = self.s_kbase if which == "k" else self.s_vbase
-        st = self.s_tk if which == "k" else self.s_tv
-        sh = {128: 7, 256: 8}[self.ROWB]
-        self.e("%s:" % label)
-        self.e("s_lshl_b32 s%d, s%d, 6" % (self.s_t2, st))
+        sh = {128: 7, 256: 8, 512: 9}[self.ROWB]
+        self.e("s_add_i32 s%d, s%d, %d" % (self.s_t2, self.s_j, ahead))
+        self.e("s_lshl_b32 s%d, s%d, %d" % (self.s_t2, self.s_t2, {32: 5, 64: 6}[self.BN]))
         for i in range(self.NLD):
             t = self.DT + (0 if which == "k" else self.NLD) + i
             self.e("v_add_u32 v%d, s%d, v%d" % (t, self.s_t2, self.DROW + i))
             self.e("v_min_i32 v%d, s%d, v%d" % (t, self.s_skvm1, t))
             self.e("v_lshlrev_b32 v%d, %d, v%d" % (t, sh, t))
+            self.e("s_mov_b32 m0, s%d" % (tab + stage * self.NLD + i))
             self.e("v_add_u32 v%d, v%d, v%d" % (t, t, self.DCH + i))
-            self.e("s_add_u32 m0, s%d, %d" % (lds, stage * self.TB + i * self.NW * 1024))
             self.e("s_nop 0")
             self.e("global_load_lds_dwordx4 v%d, %s" % (t, self.sr(base, 2)))
-        self.e("s_branch %s" % ret)
-
-    # ------------------------------------------------------- one MFMA stream
-    def stream(self, mfmas, P_prev, S_nxt, kst, vst, valu_by_slot, extra_by_slot, prefetched, nxt):
-        """Emit the slots of one iteration.
-
-        mfmas: list of ops; prefetched: how many leading operands are already in flight
-        (ids in self.outstanding); nxt: (mfma list, kst, vst) of the following iteration whose
-        first PFD operands are prefetched at the tail, or None.
-        """
-        NF, PFD = self.NF, self.PFD
-        n = len(mfmas)
-        def issue(idx, op, k, v):
-            if "halflds" in self.exp and idx % 2 == 1:
-                return
-            for ins in self.frag_loads(op, idx % NF, k, v):
-                self.e(ins)
-                self.outstanding.append(idx)
-        for i in range(prefetched, min(PFD, n)):
-            issue(i, mfmas[i], kst, vst)
-        for i, op in enumerate(mfmas):
-            # wait until every read of operand i has returned (reads return in order)
-            if "nolds" not in self.exp and any(x == i for x in self.outstanding):
-                last = max(p for p, x in enumerate(self.outstanding) if x == i)
-                after = len(self.outstanding) - 1 - last
-                self.e("s_waitcnt lgkmcnt(%d)" % after)
-                self.outstanding = self.outstanding[last + 1:]
-            self.e(self.mfma_text(op, i % NF, P_prev, S_nxt))
-            j = i + PFD
-            if j < n:
-                issue(j, mfmas[j], kst, vst)
-            elif nxt is not None:
-                nm, nk, nv = nxt
-                issue(j - n + 1000, nm[j - n], nk, nv)   # ids >= 1000: next iteration's operands
-            for ins in extra_by_slot.get(i, []):
-                self.e(ins)
-            for ins in valu_by_slot.get(i, []):
-                self.e(ins)
-        # rename the next iteration's prefetches to its own numbering
-        self.outstanding = [x - 1000 for x in self.outstanding]
-        assert "nolds" in self.exp or all(0 <= x < PFD for x in self.outstanding), self.outstanding
 
     # --------------------------------------------------------------- the loop
     def body(self, b):
-        NM, NLD = self.NM, self.NLD
-        S_cur, S_nxt = (self.SA, self.SB) if b % 2 == 0 else (self.SB, self.SA)
-        P_prev, P_new = (self.PA, self.PB) if b % 2 == 0 else (self.PB, self.PA)
+        NM = self.NM
+        S_cur, S_nxt, P_prev, P_new = self.bufs(b)
         kst, vst = (b + 1) % 4, (b + 3) % 4           # stages of K(j+1), V(j-1)
         nb = (b + 1) % 4
-        nxt = (self.mfma_list(), (nb + 1) % 4, (nb + 3) % 4)
+        nkst, nvst = (nb + 1) % 4, (nb + 3) % 4
+        groups = self.groups()
         L = self.lab
         self.e("%s:" % L("BODY%d_" % b))
-        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_ntiles))
-        self.e("s_cbranch_scc1 %s" % L("EXIT%d_" % b))
-        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_jmask))
-        self.e("s_cbranch_scc1 %s" % L("MASK%d_" % b))
-        self.e("%s:" % L("MASKRET%d_" % b))
+        # one test for everything rare: loop exit, masked tiles, loads that reach past S_kv
+        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))
+        self.e("s_cbranch_scc1 %s" % L("SPECIAL%d_" % b))
+        self.e("%s:" % L("TOP%d_" % b))               # SCC: this is a special iteration (kept up to the load slots)
         # loads of the previous iteration may stay in flight; everything older has landed
         if "nobar" not in self.exp:
-            self.e("s_waitcnt vmcnt(%d)" % (2 * NLD))
+            self.e("s_waitcnt vmcnt(%d)" % (2 * self.NLD))
             self.e("s_barrier")
-        # ---- VALU program, dealt out evenly over the slots; the row-sum test closes the last slot
-        b_ops = self.pair_ops(S_cur, P_new)
-        valu = {}
-        for i in range(NM):
-            valu[i] = b_ops[i * len(b_ops) // NM:(i + 1) * len(b_ops) // NM]
-        valu[NM - 1] = valu[NM - 1] + self.check_ops(b)
-        # ---- K(j+4) -> K stage b, V(j+2) -> V stage (b+2)%4, spread over the first slots
-        # (a fast/slow choice must not jump over other slots' work: each tensor's issue is contiguous)
+        # ---- scalar work of the slots: K(j+4) -> K stage b in slot 0, V(j+2) -> V stage (b+2)%4 in slot 1
+        # (nothing between the test above and these two branches writes SCC), pointer bumps in slot 2
         extra = {}
-        extra[0] = ["s_cmp_ge_i32 s%d, s%d" % (self.s_tk, self.s_tfull),
-                    "s_cbranch_scc1 %s" % L("KSLOW%d_" % b)]
-        for grp in self.dma_fast("k", b):
-            extra[0].extend(grp)
-        extra[0].append("%s:" % L("KRET%d_" % b))
-        extra[1] = ["s_cmp_ge_i32 s%d, s%d" % (self.s_tv, self.s_tfull),
-                    "s_cbranch_scc1 %s" % L("VSLOW%d_" % b)]
-        for grp in self.dma_fast("v", (b + 2) % 4):
-            extra[1].extend(grp)
-        extra[1].append("%s:" % L("VRET%d_" % b))
+        extra[0] = ["s_cbranch_scc1 %s" % L("KSLOW%d_" % b)] + self.dma_fast("k", b) + ["%s:" % L("KRET%d_" % b)]
+        extra[1] = ["s_cbranch_scc1 %s" % L("VSLOW%d_" % b)] + self.dma_fast("v", (b + 2) % 4) + ["%s:" % L("VRET%d_" % b)]
         extra[2] = [
             "s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kptr, self.TB),
             "s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kptr + 1),
             "s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vptr, self.TB),
             "s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vptr + 1),
-            "s_add_i32 s%d, s%d, 1" % (self.s_tk, self.s_tk),
-            "s_add_i32 s%d, s%d, 1" % (self.s_tv, self.s_tv),
             "s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j)]
-        self.stream(self.mfma_list(), P_prev, S_nxt, kst, vst, valu, extra, self.PFD, nxt)
-        # ---- deferred accumulator rescale (rare)
-        self.e("s_cmp_lg_u32 s%d, 0" % self.s_resc)
-        self.e("s_cbranch_scc1 %s" % L("RESCO%d_" % b))
-        self.e("%s:" % L("RESCORET%d_" % b))
+        if "nodma" in self.exp:
+            extra[0], extra[1] = [], []
+        # ---- VALU program: dealt out so that every slot carries about the same issue cost
+        b_ops = self.pair_ops(S_cur, P_new)
+        c_ops = self.combine_ops(S_nxt)
+        nc = 4 if c_ops else 0                        # slots reserved at the end for the combine
+        fixed = {}
+        for slot in range(NM):
+            last_of_group = slot % self.QB == self.QB - 1
+            cost = 1.0 + (1.0 if slot % self.QB == 0 else 0.0)          # MFMA (+ its s_waitcnt)
+            if last_of_group:
+                nxt_g = groups[(slot // self.QB + self.PFD) % self.NG]
+                cost += 2.0 if nxt_g[0] == "pv" else 1.0                 # LDS reads issued here
+            cost += len([x for x in extra.get(slot, []) if not x.endswith(":")])
+            fixed[slot] = cost
+        valu = spread(b_ops, fixed, NM - nc)
+        for i in range(nc):
+            valu[NM - nc + i] = c_ops[i * len(c_ops) // nc:(i + 1) * len(c_ops) // nc]
+        # the last K Q^T MFMA must be >= 11 wait states before the combine
+        assert not c_ops or (self.NPVG // 2 + self.NQKG) * self.QB <= NM - nc - 3
+        valu[NM - 1] = valu.get(NM - 1, []) + self.check_ops(b)     # the row-sum test closes the last slot
+        self.stream(groups,
+                    lambda g, buf: self.mfma_texts(g, buf, P_prev, S_nxt),
+                    lambda g, buf: self.frag_loads(g, buf, kst, vst),
+                    self.NF, self.PFD, valu, extra,
+                    lambda i, buf: self.frag_loads(groups[i], buf, nkst, nvst))
         if b == 3:
             self.e("s_branch %s" % L("BODY0_"))
 
     def out_of_line(self, b):
         L = self.lab
-        S_cur = self.SA if b % 2 == 0 else self.SB
-        # ---- mask pre-pass: keys past the causal diagonal / past S_kv become -inf
-        self.e("%s:" % L("MASK%d_" % b))
-        self.e("s_lshl_b32 s%d, s%d, 6" % (self.s_t2, self.s_j))
-        self.e("v_subrev_u32 v%d, s%d, v%d" % (self.THR, self.s_t2, self.THRB))  # limit - 4g - 64 j
+        S_cur, S_nxt, P_prev, P_new = self.bufs(b)
+        QB = self.QB
+        # ---- rare iterations: past the last tile?  a tile that needs a mask?  (its loads: KSLOW / VSLOW)
+        self.e("%s:" % L("SPECIAL%d_" % b))
+        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_ntiles))
+        self.e("s_cbranch_scc1 %s" % L("EXIT%d_" % b))
+        self.e("s_cmp_lt_i32 s%d, s%d" % (self.s_j, self.s_jmask))
+        self.e("s_cbranch_scc1 %s" % L("NOMASK%d_" % b))
+        # mask pre-pass: keys past the causal diagonal / past S_kv become -inf
+        self.e("s_lshl_b32 s%d, s%d, %d" % (self.s_t2, self.s_j, {32: 5, 64: 6}[self.BN]))
         self.e("v_mov_b32 v%d, 0xff800000" % self.NEGINF)
-        for el in range(32):
-            sb, r = el // 16, el % 16
-            const = 32 * sb + 8 * (r >> 2) + (r & 3)
-            self.e("v_cmp_gt_i32 vcc, %d, v%d" % (const, self.THR))       # key index > limit ?
-            self.e("v_cndmask_b32 v%d, v%d, v%d, vcc" % (S_cur + el, S_cur + el, self.NEGINF))
-        self.e("s_branch %s" % L("MASKRET%d_" % b))
-        # ---- the tile's row sum failed the test: exact row maximum of the (intact) scores, move the
-        # reference there (alpha = exp2((m_ref - m_new) c); 0 when m_ref was still -inf), redo the tile's P
-        P_new = self.PB if b % 2 == 0 else self.PA
+        for qb in range(QB):
+            self.e("v_subrev_u32 v%d, s%d, v%d" % (self.THR + qb, self.s_t2, self.THRB + qb))  # limit - 4g - BN j
+        for qb in range(QB):
+            for sb in range(self.SB):
+                for r in range(16):
+                    const = 32 * sb + 8 * (r >> 2) + (r & 3)
+                    x = self.s_reg(S_cur, qb, sb, 0, r)
+                    self.e("v_cmp_gt_i32 vcc, %d, v%d" % (const, self.THR + qb))       # key index > limit ?
+                    self.e("v_cndmask_b32 v%d, v%d, v%d, vcc" % (x, x, self.NEGINF))
+        self.e("%s:" % L("NOMASK%d_" % b))
+        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))                    # SCC = 1 again
+        self.e("s_branch %s" % L("TOP%d_" % b))
+        # ---- a tile row sum failed the test: exact row maxima of the (intact) scores, move the references
+        # there (alpha = exp2((m_ref - m_new) c); 0 when m_ref was still -inf), redo the tile's P, and scale
+        # the accumulators (every MFMA of the iteration has been issued; wait for the last to retire)
         self.e("%s:" % L("SLOW%d_" % b))
         for ins in self.max_ops(S_cur) + self.pairmax_ops():
             self.e(ins)
-        self.e("v_sub_f32 v%d, v%d, v%d" % (self.DD, self.MREF, self.T))
-        self.e("v_mul_f32 v%d, s%d, v%d" % (self.DD, self.s_c, self.DD))
-        self.e("v_exp_f32 v%d, v%d" % (self.ALPHA, self.DD))
-        self.e("v_mov_b32 v%d, v%d" % (self.MREF, self.T))
-        self.e("v_mul_f32 v%d, s%d, v%d" % (self.MRC, self.s_c, self.T))
+        for qb in range(QB):
+            self.e("v_sub_f32 v%d, v%d, v%d" % (self.DD + qb, self.MREF + qb, self.T + qb))
+            self.e("v_mul_f32 v%d, s%d, v%d" % (self.DD + qb, self.s_c, self.DD + qb))
+            self.e("v_exp_f32 v%d, v%d" % (self.ALPHA + qb, self.DD + qb))
+            self.e("v_mov_b32 v%d, v%d" % (self.MREF + qb, self.T + qb))
+            self.e("v_mul_f32 v%d, s%d, v%d" % (self.MRC + qb, self.s_c, self.T + qb))
         self.e("s_nop 1")
-        self.e("v_mul_f32 v%d, v%d, v%d" % (self.L, self.L, self.ALPHA))
-        self.e("s_mov_b32 s%d, 1" % self.s_resc)
+        for qb in range(QB):
+            self.e("v_mul_f32 v%d, v%d, v%d" % (self.L + qb, self.L + qb, self.ALPHA + qb))
         for ins in self.pair_ops(S_cur, P_new):
+            self.e(ins)
+        self.e("s_nop 15")
+        for ins in self.rescale_o_ops():
             self.e(ins)
         self.e("s_nop 7")
         self.e("s_branch %s" % L("SLOWRET%d_" % b))
-        # ---- O *= alpha once every MFMA of P(j-1) V(j-1) has been issued and has retired
-        self.e("%s:" % L("RESCO%d_" % b))
-        self.e("s_nop 15")
-        self.e("s_nop 7")
-        for i in range(16 * self.DB):
-            self.e("v_mul_f32 v%d, v%d, v%d" % (self.O + i, self.ALPHA, self.O + i))
-        self.e("s_mov_b32 s%d, 0" % self.s_resc)
-        self.e("s_nop 7")
-        self.e("s_branch %s" % L("RESCORET%d_" % b))
         # ---- ragged-tile loads
-        self.dma_slow("k", b, L("KSLOW%d_" % b), L("KRET%d_" % b))
-        self.dma_slow("v", (b + 2) % 4, L("VSLOW%d_" % b), L("VRET%d_" % b))
+        self.e("%s:" % L("KSLOW%d_" % b))
+        if "nodma" not in self.exp:
+            self.dma_slow("k", b, 4)
+        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))                    # SCC = 1 for the V slot
+        self.e("s_branch %s" % L("KRET%d_" % b))
+        self.e("%s:" % L("VSLOW%d_" % b))
+        if "nodma" not in self.exp:
+            self.dma_slow("v", (b + 2) % 4, 2)
+        self.e("s_branch %s" % L("VRET%d_" % b))
 
     def drain(self, b):
-        """Loop exit taken at the top of iteration b: O += P(n-1) V(n-1), operands of the first
-        PFD MFMAs were prefetched by the previous iteration."""
+        """Loop exit taken at the top of iteration b: O += P(n-1) V(n-1); the operands of the first PFD
+        groups were prefetched by the previous iteration."""
         L = self.lab
-        P_prev = self.PA if b % 2 == 0 else self.PB
+        S_cur, S_nxt, P_prev, P_new = self.bufs(b)
         vst = (b + 3) % 4
-        pv = [("pv", kc, db) for kc in range(4) for db in range(self.DB)]
+        pv = [("pv", kc, db) for kc in range(2 * self.SB) for db in range(self.DB)]
         self.e("%s:" % L("EXIT%d_" % b))
-        # the prefetched operands belong to the interleaved order (first half of PV only): same ops
-        self.outstanding = [i for i in range(self.PFD) for _ in range(2) if not ("halflds" in self.exp and i % 2 == 1)]
-        self.stream(pv, P_prev, 0, 0, vst, {}, {}, self.PFD, None)
+        # the prefetched operands belong to the interleaved order (first half of P V only): same groups
+        self.outstanding = [i for i in range(self.PFD) for _ in range(2)] if "nolds" not in self.exp else []
+        self.stream(pv, lambda g, buf: self.mfma_texts(g, buf, P_prev, 0),
+                    lambda g, buf: self.frag_loads(g, buf, 0, vst), self.NF, self.PFD, {}, {}, None)
         self.e("s_branch %s" % L("DONE_"))
 
     def generate(self):
         L = self.lab
         e = self.e
+        QB = self.QB
         e("s_nop 15")
         e("s_nop 7")
-        e("s_mov_b32 s%d, m0" % self.s_m0)
+        self.save_m0(self.s_m0)
         e("s_mov_b32 s%d, 0" % self.s_j)
-        e("s_mov_b32 s%d, 0" % self.s_resc)
         e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, self.tau_bits()))   # bound on a tile's row sum
+        # first iteration that is not plain: min(first masked tile, first tile whose K load (4 tiles ahead)
+        # reaches past S_kv, n_tiles)
+        e("s_sub_i32 s%d, s%d, 4" % (self.s_special, self.s_tfull))
+        e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_jmask))
+        e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_ntiles))
         e("s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kbase, 4 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kbase + 1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vbase, 2 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vbase + 1))
-        e("s_mov_b32 s%d, 4" % self.s_tk)
-        e("s_mov_b32 s%d, 2" % self.s_tv)
-        for i in range(16):
-            e("v_mov_b32 v%d, 0" % (self.PA + i))                # P(-1) = 0
-        e("v_mov_b32 v%d, 0xff800000" % self.MREF)              # no reference yet: the first tile's test fails
-        e("v_mov_b32 v%d, 0xff800000" % self.MRC)
-        e("v_mov_b32 v%d, 0" % self.L)
-        e("v_mov_b32 v%d, 1.0" % self.ALPHA)
-        # operands of the first PFD MFMAs of iteration 0 ("V(-1)" lives in stage 3)
+        for st in range(4):
+            for i in range(self.NLD):
+                off = st * self.TB + i * self.NW * 1024
+                e("s_add_u32 s%d, s%d, %d" % (self.s_lk + st * self.NLD + i, self.s_ldsk, off))
+                e("s_add_u32 s%d, s%d, %d" % (self.s_lv + st * self.NLD + i, self.s_ldsv, off))
+        for i in range(8 * QB * self.SB):
+            e("v_mov_b32 v%d, 0" % (self.PA + i))                    # P(-1) = 0
+        for qb in range(QB):
+            e("v_mov_b32 v%d, 0xff800000" % (self.MREF + qb))        # no reference yet: the first tile's test fails
+            e("v_mov_b32 v%d, 0xff800000" % (self.MRC + qb))
+            e("v_mov_b32 v%d, 0" % (self.L + qb))
+            e("v_mov_b32 v%d, 1.0" % (self.ALPHA + qb))
+        # operands of the first PFD groups of iteration 0 ("V(-1)" lives in stage 3)
         self.outstanding = []
-        m0 = self.mfma_list()
+        g0 = self.groups()
+        assert all(g[0] == "pv" for g in g0[:self.PFD])
         for i in range(self.PFD):
-            for ins in self.frag_loads(m0[i], i % self.NF, 1, 3):
-                e(ins)
-                self.outstanding.append(i)
+            self.lds_issue(i, self.frag_loads(g0[i], i % self.NF, 1, 3))
         for b in range(4):
             self.body(b)
         for b in range(4):
@@ -477,38 +556,37 @@ class Gen:
             self.drain(b)
         e("%s:" % L("DONE_"))
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
-        e("s_mov_b32 m0, s%d" % self.s_m0)
+        self.restore_m0(self.s_m0)
         e("s_nop 15")
         e("s_nop 7")
 
     # ----------------------------------------------------------- C++ wrapper
     def emit_inc(self):
         self.generate()
-        D, DB, KS = self.D, self.DB, self.KS
+        D, DB, KS, QB, SB = self.D, self.DB, self.KS, self.QB, self.SB
         out = []
-        out.append("// Generated by gen_attn_loop.py %d %s -- do not edit.  Main loop of attn_fwd_asm_kernel<%d, *> (%s)." % (D, self.dtype, D, self.dtype))
-        out.append("// VGPRs used: %d.  MFMA slots per iteration: %d." % (self.NV, self.NM))
+        out.append("// Generated by gen_attn_loop.py %s %s -- do not edit.  Main loop of attn_fwd_asm_kernel (D = %d, %d waves x %d rows, %d-key tiles)."
+                   % (self.name, self.dtype, D, self.NW, 32 * QB, self.BN))
+        out.append("// VGPRs used: %d, AGPRs used: %d.  MFMA slots per iteration: %d." % (self.NV, self.NA, self.NM))
         out.append("asm volatile(")
         for ln in self.lines:
             out.append('    "%s\\n\\t"' % ln)
-        # outputs
-        outs = []
-        for db in range(DB):
-            outs.append('"+{%s}"(o_acc[%d])' % (self.vr(self.O + 16 * db, 16), db))
-        outs.append('"+{%s}"(s_init[0])' % self.vr(self.SA, 16))
-        outs.append('"+{%s}"(s_init[1])' % self.vr(self.SA + 16, 16))
-        outs.append('"={%s}"(m_ref)' % self.vr(self.MREF))
-        outs.append('"={%s}"(l_run)' % self.vr(self.L))
-        ins = []
-        nq = 4 * KS // 16
-        for i in range(nq):
-            ins.append('"{%s}"(q_pack[%d])' % (self.vr(self.Q + 16 * i, 16), i))
+        outs, ins = [], []
+        for i in range(QB * DB):
+            outs.append('"+{%s}"(o_acc[%d])' % (self.acc(self.O + 16 * i, 16), i))
+        for qb in range(QB):
+            for sb in range(SB):
+                outs.append('"+{%s}"(s_init[%d])' % (self.vr(self.s_reg(self.SA, qb, sb), 16), qb * SB + sb))
+        outs.append('"={%s}"(m_ref_v)' % self.vr(self.MREF, QB))
+        outs.append('"={%s}"(l_run_v)' % self.vr(self.L, QB))
+        for i in range(4 * QB * KS // 16):
+            ins.append('"{%s}"(q_pack[%d])' % (self.acc(self.Q + 16 * i, 16), i))
         ins.append('"{%s}"(koff_v)' % self.vr(self.KOFF, KS))
         ins.append('"{%s}"(voff_v)' % self.vr(self.VOFF, 2 * DB))
         ins.append('"{%s}"(dma_voff_v)' % self.vr(self.DVOFF, self.NLD))
         ins.append('"{%s}"(dma_row_v)' % self.vr(self.DROW, self.NLD))
         ins.append('"{%s}"(dma_choff_v)' % self.vr(self.DCH, self.NLD))
-        ins.append('"{%s}"(thr_base)' % self.vr(self.THRB))
+        ins.append('"{%s}"(thr_base_v)' % self.vr(self.THRB, QB))
         ins.append('"{%s}"(k_head)' % self.sr(self.s_kbase, 2))
         ins.append('"{%s}"(v_head)' % self.sr(self.s_vbase, 2))
         ins.append('"{s%d}"(c_log2e)' % self.s_c)
@@ -519,37 +597,42 @@ class Gen:
         ins.append('"{s%d}"(lds_k_wave)' % self.s_ldsk)
         ins.append('"{s%d}"(lds_v_wave)' % self.s_ldsv)
         pinned = set()
-        for db in range(DB):
-            pinned.update(range(self.O + 16 * db, self.O + 16 * db + 16))
-        pinned.update(range(self.SA, self.SA + 32))
-        pinned.update([self.MREF, self.L, self.THRB])
-        pinned.update(range(self.Q, self.Q + 4 * KS))
-        pinned.update(range(self.KOFF, self.KOFF + KS))
-        pinned.update(range(self.VOFF, self.VOFF + 2 * DB))
-        pinned.update(range(self.DVOFF, self.DVOFF + self.NLD))
-        pinned.update(range(self.DROW, self.DROW + self.NLD))
-        pinned.update(range(self.DCH, self.DCH + self.NLD))
+        if not self.AG:
+            pinned.update(range(self.O, self.O + 16 * QB * DB))
+            pinned.update(range(self.Q, self.Q + 4 * QB * KS))
+        for qb in range(QB):
+            for sb in range(SB):
+                pinned.update(range(self.s_reg(self.SA, qb, sb), self.s_reg(self.SA, qb, sb) + 16))
+        for base, n in ((self.MREF, QB), (self.L, QB), (self.THRB, QB), (self.KOFF, KS), (self.VOFF, 2 * DB),
+                        (self.DVOFF, self.NLD), (self.DROW, self.NLD), (self.DCH, self.NLD)):
+            pinned.update(range(base, base + n))
         clob = ['"memory"', '"vcc"', '"scc"']
         clob += ['"v%d"' % i for i in range(self.NV) if i not in pinned]
-        clob += ['"s%d"' % i for i in range(self.s_j, self.s_m0 + 1)]
+        clob += ['"s%d"' % i for i in range(self.s_j, self.s_last + 1)]
+        if "sgprcheck" in self.exp:
+            clob += ['"s96"', '"s97"']
         out.append("    : " + ", ".join(outs))
         out.append("    : " + ", ".join(ins))
         out.append("    : " + ", ".join(clob) + ");")
         return "\n".join(out) + "\n"
 
 
-if __name__ == "__main__":
-    args = sys.argv[1:]
-    pfd, drop = 3, ()
-    while len(args) > 2 and args[-2] in ("--pfd", "--drop"):
+def main(argv):
+    args = list(argv)
+    kw = {}
+    while len(args) > 2 and args[-2] in ("--pfd", "--nf", "--drop"):
         if args[-2] == "--pfd":
-            pfd = int(args[-1])
+            kw["PFD"] = int(args[-1])
+        elif args[-2] == "--nf":
+            kw["NF"] = int(args[-1])
         else:
-            drop = tuple(filter(None, args[-1].split(",")))
+            kw["drop"] = tuple(filter(None, args[-1].split(",")))
         args = args[:-2]
-    D = int(args[0])
     dtype = args[2] if len(args) > 2 else "bf16"
-    nw = int(args[3]) if len(args) > 3 else 8
-    text = Gen(D, PFD=pfd, dtype=dtype, NW=nw, drop=drop).emit_inc()
+    text = Gen(args[0], dtype=dtype, **kw).emit_inc()
     with open(args[1], "w") as f:
         f.write(text)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:])

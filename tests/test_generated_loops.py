@@ -1,0 +1,88 @@
+"""The generated instruction streams (csrc/gen_attn_loop.py, csrc/gen_attn_bwd_loop.py) obey the rules the
+hardware does not enforce, checked on the emitted text itself (asm_emit.check_stream): every register filled
+by an LDS read is covered by an s_waitcnt before its first use, MFMA results are not touched by the VALU
+within 11 wait states, VALU results not read by an MFMA within 2, transcendental results not used by the
+next instruction, one wait state between a scalar write of m0 and a direct global->LDS load.  The main path
+is walked twice round the four loop bodies (loop-carried distances), and once through every out-of-line
+section (mask pre-pass, exact-maximum pass, ragged loads, each loop exit).  Also: the library build's
+generated files are exactly what the generators emit, with or without stray environment variables."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2512_18134_amd", "csrc")
+sys.path.insert(0, CSRC)
+
+import asm_emit  # noqa: E402
+import gen_attn_loop  # noqa: E402
+
+FWD = [(name, dt) for name in gen_attn_loop.CONFIGS for dt in ("bf16", "f16")]
+
+
+def fwd_lines(name, dtype="bf16"):
+    g = gen_attn_loop.Gen(name, dtype=dtype)
+    g.generate()
+    return [l.replace("%=", "") for l in g.lines]
+
+
+@pytest.mark.parametrize("name,dtype", FWD)
+def test_forward_main_path_twice_round(name, dtype):
+    lines = fwd_lines(name, dtype)
+    path = asm_emit.walk(lines, loop_label="BODY0_", loop_visits=2)
+    n_mfma = sum(1 for l in path if l.startswith("v_mfma"))
+    g = gen_attn_loop.Gen(name)
+    assert n_mfma == 2 * 4 * g.NM                      # two full rounds of the four bodies
+    assert asm_emit.check_stream(path) == len(path)
+
+
+@pytest.mark.parametrize("name", list(gen_attn_loop.CONFIGS))
+@pytest.mark.parametrize("b", range(4))
+def test_forward_out_of_line_sections(name, b):
+    lines = fwd_lines(name)
+    # each detour is taken the first time its branch is met (body b of the first round; the bodies are
+    # alike, so b = 1..3 also cover a detour with loop-carried state before it), then the loop goes on
+    for detour in (["SLOW%d_" % b], ["SPECIAL%d_" % b, "KSLOW%d_" % b, "VSLOW%d_" % b],
+                   ["SPECIAL%d_" % b, "NOMASK%d_" % b, "KSLOW%d_" % b, "VSLOW%d_" % b],
+                   ["SPECIAL%d_" % b, "EXIT%d_" % b]):
+        path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=2)
+        assert asm_emit.check_stream(path) == len(path)
+        if "EXIT%d_" % b in detour:
+            assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
+
+
+def test_checker_catches_planted_mistakes():
+    lines = fwd_lines("d128")
+    path = asm_emit.walk(lines, loop_label="BODY0_", loop_visits=2)
+    # a wait removed: the fragment of the next MFMA is then read while its LDS read is in flight
+    i = [k for k, l in enumerate(path) if l.startswith("s_waitcnt lgkmcnt")][5]
+    with pytest.raises(AssertionError):
+        asm_emit.check_stream(path[:i] + path[i + 1:])
+    # a VALU read of a score block moved right behind the MFMA that produces it
+    k = [k for k, l in enumerate(path) if l.startswith("v_mfma") and ", 0" not in l and "v[128:143]" in l.split(",")[0]]
+    with pytest.raises(AssertionError):
+        asm_emit.check_stream(path[:k[0] + 1] + ["v_add_f32 v250, v128, v128"] + path[k[0] + 1:])
+    # the filler between an m0 write and its load removed
+    j = [k for k, l in enumerate(path) if l.startswith("global_load_lds")][0]
+    with pytest.raises(AssertionError):
+        asm_emit.check_stream(path[:j - 1] + path[j:])
+    # exp result consumed by the very next instruction
+    x = [k for k, l in enumerate(path) if l.startswith("v_exp_f32")][0]
+    dst = path[x].split()[1].rstrip(",")
+    with pytest.raises(AssertionError):
+        asm_emit.check_stream(path[:x + 1] + ["v_add_f32 v250, %s, %s" % (dst, dst)] + path[x + 1:])
+
+
+def test_build_output_is_the_generators_output_and_ignores_the_environment(tmp_path):
+    from paper_2512_18134_amd import build
+    env = dict(os.environ, ATTN_GEN_EXP="novalu", ATTN_GEN_BWD_EXP="nolds", ATTN_GEN_TAU="3", ATTN_GEN_PFD="2")
+    code = ("import sys; sys.path.insert(0, %r)\nfrom paper_2512_18134_amd import build\n"
+            "build.generate_sources(out_dir=%r)\n" % (ROOT, str(tmp_path)))
+    subprocess.run([sys.executable, "-c", code], check=True, env=env)
+    committed = os.path.join(CSRC, "generated")
+    names = sorted(os.listdir(str(tmp_path)))
+    assert names == sorted(f for f in os.listdir(committed) if f.endswith(".inc")) and len(names) >= 17
+    for fn in names:
+        assert open(os.path.join(str(tmp_path), fn)).read() == open(os.path.join(committed, fn)).read(), fn
