@@ -1,8 +1,11 @@
 #!/usr/bin/env python3
 """Bench: Flash-Attention forward on one MI355X, headline workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+    python bench.py --config N                          # baseline workloads 1..5 (4 = headline)
+    python bench.py --config 4 --inputs zeros           # same launch on all-zero tensors (power-limit evidence)
     python bench.py --paper-seq 16384 [--dtype f16]     # the paper's own sweep shape (Section 6.2)
+    python bench.py --probe-mfma                        # matrix-pipe ceiling: MFMA-only loop of the debug build
 
 A "step" is one attn_fwd call (the whole hot path) over one batch of seeded
 synthetic Q/K/V that is already resident in HBM.  Prints ONE JSON line.
@@ -130,12 +133,57 @@ def bench_bwd(args, cfg, qd, kd, vd, scale, stream, fwd_flops, host_qkv):
     print(json.dumps(out), flush=True)
 
 
+def probe_mfma(args, dev):
+    """Matrix-pipe ceiling: the MFMA-only loop of the debug build (attn_probe_mfma: no LDS, no VALU work, no
+    memory traffic), 256 CUs x 4 workgroups, one or two waves per SIMD, on random N(0,1), constant and zero bf16
+    operands.  Prints one JSON line; run it under rocprofv3 --pmc GRBM_GUI_ACTIVE for the clock."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "paper_2512_18134_amd", "libmi355attn_debug.so")
+    lib = ctypes.CDLL(path)
+    lib.attn_probe_mfma.restype = ctypes.c_int
+    lib.attn_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    stream = torch.cuda.current_stream(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    n_wg, iters = 1024, 4096
+    res = {}
+    for waves in (4, 8):
+        out = torch.empty((n_wg * waves * 64,), dtype=torch.float32, device=dev)
+        for kind in ("random", "constant", "zero"):
+            ops = {"random": torch.randn((8 * 64 * 8,), generator=gen, device=dev, dtype=torch.float32),
+                   "constant": torch.full((8 * 64 * 8,), 1.0, device=dev),
+                   "zero": torch.zeros((8 * 64 * 8,), device=dev)}[kind].to(torch.bfloat16)
+            call = lambda: lib.attn_probe_mfma(ops.data_ptr(), out.data_ptr(), n_wg, waves, iters, stream.cuda_stream)
+            for _ in range(3):
+                assert call() == 0
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for e0, e1 in evs:
+                e0.record(stream)
+                call()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+            flop = float(n_wg) * waves * iters * 8 * 32768
+            res["%d_waves_per_simd_%s" % (waves // 4, kind)] = {"ms": ms, "tflops": flop / ms / 1e9,
+                                                               "frac_of_peak": flop / ms / 1e9 / PEAK_BF16_TFLOPS}
+    print(json.dumps({"probe": "v_mfma_f32_32x32x16_bf16 issue ceiling (registers only)", "n_wg": n_wg,
+                      "iters": iters, "results": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, help="index into the baseline configs (3 = headline D=128 S=16384)")
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5],
+                    help="baseline workload 1..5 (4 = headline D=128 S=16384 non-causal)")
+    ap.add_argument("--inputs", choices=["synth", "zeros"], default="synth",
+                    help="zeros: time the same launch on all-zero q, k, v (the matrix pipe then toggles no operand "
+                         "bits: what the schedule sustains when the chip is not power limited)")
+    ap.add_argument("--probe-mfma", action="store_true",
+                    help="time the MFMA-only loop of the debug build on random, constant and zero operands")
     ap.add_argument("--paper-seq", type=int, default=0,
                     help="time the paper's Section 6.2 shape (B=4, H=32, D=128, non-causal) at this sequence length")
     ap.add_argument("--causal", action="store_true", help="with --paper-seq: the causal variant of that shape")
@@ -172,6 +220,8 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": args.steps}))
         return
     dev = torch.device("cuda:0")
+    if args.probe_mfma:
+        return probe_mfma(args, dev)
     if args.splitkv:
         cfg = dict(name="long_B1_H8_Sq256_Skv%d_D128_full_split%d" % (args.long_skv, args.splitkv), B=1, H=8, S_q=256,
                    S_kv=args.long_skv, D=128, causal=False, seed=300, sharp=False, dtype="bf16")
@@ -204,6 +254,10 @@ def main():
             cfg["name"] += "_f16"
         to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(tdt)
         qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    if args.inputs == "zeros":
+        qd, kd, vd = torch.zeros_like(qd), torch.zeros_like(kd), torch.zeros_like(vd)
+        cfg = dict(cfg, name=cfg["name"] + "_zero_inputs")
+        q = k = v = None
     entry = binding.attn_fwd_f16 if cfg["dtype"] == "f16" else binding.attn_fwd
     o = torch.empty_like(qd)
     lse = torch.empty(qd.shape[:3], dtype=torch.float32, device=dev)

@@ -61,19 +61,27 @@ class Emitter:
         self.outstanding = self.outstanding[last + 1:]
 
     # ------------------------------------------------------------ MFMA stream
-    def stream(self, groups, mfma_texts, frag_loads, NF, PFD, valu_by_slot, extra_by_slot, nxt_frag_loads):
+    def stream(self, groups, mfma_texts, frag_loads, NF, PFD, valu_by_slot, extra_by_slot, nxt_frag_loads,
+               prefetched=None, wait_every=1):
         """Emit the slots of one iteration.
 
         groups: fragment groups in issue order; mfma_texts(g, buf) -> the MFMAs fed by group g's fragment
         (buffer buf); frag_loads(g, buf) -> the LDS reads that fill it; nxt_frag_loads(i, buf) -> reads of
         group i of the NEXT iteration (prefetched in the last PFD groups) or None when there is none.
-        The first PFD groups' reads are already in flight (ids 0..PFD-1 in self.outstanding).
-        A slot is one MFMA; extras and VALU shares are keyed by slot number.
+        The reads of the first `prefetched` groups (default PFD) are already in flight (ids 0.. in
+        self.outstanding); the rest up to PFD is issued first.  wait_every = W: one s_waitcnt per W groups,
+        for the operands of all W (needs PFD >= W).  A slot is one MFMA; extras and VALU shares are keyed by
+        slot number.
         """
         n = len(groups)
+        prefetched = PFD if prefetched is None else prefetched
+        assert PFD >= wait_every and PFD < NF
+        for i in range(prefetched, min(PFD, n)):
+            self.lds_issue(i, frag_loads(groups[i], i % NF))
         slot = 0
         for i, g in enumerate(groups):
-            self.lds_wait(i)
+            if i % wait_every == 0:
+                self.lds_wait(min(i + wait_every - 1, n - 1))
             texts = mfma_texts(g, i % NF)
             for t, text in enumerate(texts):
                 self.e(text)
@@ -91,7 +99,7 @@ class Emitter:
                 slot += 1
         # the next iteration's prefetches take its own numbering
         self.outstanding = [x - 1000 for x in self.outstanding]
-        assert all(0 <= x < PFD for x in self.outstanding), self.outstanding
+        assert nxt_frag_loads is None or all(0 <= x < PFD for x in self.outstanding), self.outstanding
         return slot
 
     # ------------------------------------------------------------------- m0
@@ -210,8 +218,10 @@ def check_stream(lines, mfma_to_valu=11, valu_to_mfma=2, trans_to_use=1, m0_to_d
             t += 1
             continue
         if op.startswith("ds_read"):
+            for p in pending:      # LDS reads return in order: a later read into the same registers wins
+                p -= dst
             for p in pending:
-                assert not (p & dst), "LDS read overwrites a register still in flight: %s" % ins
+                assert not (p & src), "address register still in flight: %s" % ins
             pending.append(set(dst))
             t += 1
             continue

@@ -9,6 +9,9 @@
 #include "attn_fwd_asm.h"
 #include "attn_fwd_simple.h"
 #include "attn_launch.h"
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+#include "attn_probe.h"
+#endif
 #include "attn_splitkv.h"
 
 namespace {
@@ -293,6 +296,26 @@ extern "C" int attn_fwd_variant(const void *q, const void *k, const void *v, voi
         return D == 64 && asm_ok ? launch_d64(p, B * H, causal, st, variant - 3) : ATTN_ERR_UNSUPPORTED;
     }
     return ATTN_ERR_UNSUPPORTED;
+}
+#endif
+
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+// Measurement entry point of the debug build: n_wg workgroups of waves_per_wg (4 or 8) waves, each wave
+// `iters` x 8 MFMAs (32768 FLOP each) on the 8 fragments at `operands` (device, 8 * 64 * 16 bytes: 4 A then 4 B
+// fragments, 16 bytes per lane); `out` (device, n_wg * waves_per_wg * 64 floats) receives one value per lane.
+extern "C" int attn_probe_mfma(const void *operands, float *out, int n_wg, int waves_per_wg, int iters, void *stream)
+{
+    if (!operands || !out)
+        return ATTN_ERR_NULL;
+    if (n_wg < 1 || iters < 1 || (waves_per_wg != 4 && waves_per_wg != 8))
+        return ATTN_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const attn::bf16x8 *ops = static_cast<const attn::bf16x8 *>(operands);
+    if (waves_per_wg == 4)
+        hipLaunchKernelGGL(attn::attn_probe_mfma_kernel<4>, dim3(n_wg), dim3(256), 0, st, ops, out, iters);
+    else
+        hipLaunchKernelGGL(attn::attn_probe_mfma_kernel<8>, dim3(n_wg), dim3(512), 0, st, ops, out, iters);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 #endif
 

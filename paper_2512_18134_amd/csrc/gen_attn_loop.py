@@ -62,8 +62,8 @@ are re-checked on the emitted text by asm_emit.check_stream in the tests):
   * scalar write of m0 -> direct load needs 1 wait state: an s_nop goes between
     them.
 
-usage: gen_attn_loop.py <config> <out.inc> [bf16|f16] [--pfd N] [--nf N] [--drop part,part]
-(--pfd, --nf and --drop exist for timing experiments; a library build passes none)
+usage: gen_attn_loop.py <config> <out.inc> [bf16|f16] [--pfd N] [--nf N] [--w N] [--drop part,part]
+(--pfd, --nf, --w and --drop exist for timing experiments; a library build passes none)
 """
 import os
 import struct
@@ -74,19 +74,23 @@ from asm_emit import Emitter, spread  # noqa: E402
 
 CONFIGS = {
     # D: head dimension; QB: 32-row query blocks per wave; SB: 32-key blocks per K/V tile; NW: waves per
-    # workgroup; AG: O and Q in AGPRs (one wave per SIMD); NACC: K Q^T accumulators per score block
-    "d64":    dict(D=64,  QB=1, SB=2, NW=8, AG=False, NACC=1),
-    "d64_w4": dict(D=64,  QB=1, SB=2, NW=4, AG=False, NACC=1),
-    "d128":   dict(D=128, QB=1, SB=2, NW=8, AG=False, NACC=1),
-    "d128a":  dict(D=128, QB=2, SB=1, NW=4, AG=True,  NACC=1),
-    "d256a":  dict(D=256, QB=1, SB=1, NW=4, AG=True,  NACC=2),
+    # workgroup; AG: O and Q in AGPRs (one wave per SIMD); NACC: K Q^T accumulators per score block;
+    # NF: fragment buffers; PFD: groups between a fragment's LDS read and its MFMA; W: groups per s_waitcnt
+    "d64":    dict(D=64,  QB=1, SB=2, NW=8, AG=False, NACC=1, NF=8, PFD=6, W=2),
+    "d64_w4": dict(D=64,  QB=1, SB=2, NW=4, AG=False, NACC=1, NF=8, PFD=6, W=2),
+    "d128":   dict(D=128, QB=1, SB=2, NW=8, AG=False, NACC=1, NF=4, PFD=3, W=1),
+    "d128a":  dict(D=128, QB=2, SB=1, NW=4, AG=True,  NACC=1, NF=8, PFD=7, W=4),
+    "d256a":  dict(D=256, QB=1, SB=1, NW=4, AG=True,  NACC=2, NF=8, PFD=7, W=4),
 }
 
 
 class Gen(Emitter):
-    def __init__(self, name, dtype="bf16", NF=4, PFD=3, drop=()):
+    def __init__(self, name, dtype="bf16", NF=None, PFD=None, W=None, drop=()):
         Emitter.__init__(self)
         cfg = CONFIGS[name]
+        NF = cfg["NF"] if NF is None else NF
+        PFD = cfg["PFD"] if PFD is None else PFD
+        self.W = cfg["W"] if W is None else W
         assert dtype in ("bf16", "f16")
         self.name, self.dtype = name, dtype
         # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
@@ -106,7 +110,7 @@ class Gen(Emitter):
         self.NQKG = self.KS * SB                  # fragment groups of K Q^T
         self.NG = self.NPVG + self.NQKG
         self.NM = self.NG * QB                    # MFMA slots per iteration
-        assert self.NG % NF == 0 and PFD < NF
+        assert self.NG % NF == 0 and self.W <= PFD < NF and self.NG % self.W == 0
         # timing experiments only (results are wrong with any of these set): parts of the loop to leave out
         self.exp = set(drop)
         # ---- register map
@@ -134,7 +138,7 @@ class Gen(Emitter):
         self.L = take(QB)                 # running row sums (this lane's half of the keys)
         self.TLA = take(QB)               # row sums of the current tile, two partial sums each
         self.TLB = take(QB)
-        self.TP = take(6)                 # exponent / exp temporaries of three element pairs in flight
+        self.TP = take(8)                 # exponent / exp temporaries: four element pairs (three in flight)
         self.ALPHA = take(QB)
         self.THRB = take(QB)
         self.THR = take(QB)
@@ -236,7 +240,7 @@ class Gen(Emitter):
         The exponent arguments go to the temporaries TP: S_cur stays intact for the out-of-line pass."""
         pairs = self.pairs()
         def tp(t, i):
-            return self.TP + 2 * (t % 3) + i
+            return self.TP + 2 * (t % 4) + i
         def F(t):
             qb = pairs[t][0]
             return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (tp(t, i), x, self.s_c, self.MRC + qb)
@@ -245,8 +249,11 @@ class Gen(Emitter):
             return ["v_exp_f32 v%d, v%d" % (tp(t, i), tp(t, i)) for i in (0, 1)]
         def A(t):
             qb, k = pairs[t]
-            if k == 0:   # the first pair of a query block starts its two partial sums
-                acc = ["v_mov_b32 v%d, v%d" % (self.TLA + qb, tp(t, 0)), "v_mov_b32 v%d, v%d" % (self.TLB + qb, tp(t, 1))]
+            if k == 0:     # the partial sums of a query block start with its first two pairs (next step)
+                acc = []
+            elif k == 1:   # the temporaries of pair t-1 are still intact: four sets, three pairs in flight
+                acc = ["v_add_f32 v%d, v%d, v%d" % (self.TLA + qb, tp(t - 1, 0), tp(t, 0)),
+                       "v_add_f32 v%d, v%d, v%d" % (self.TLB + qb, tp(t - 1, 1), tp(t, 1))]
             else:
                 acc = ["v_add_f32 v%d, v%d, v%d" % (self.TLA + qb, self.TLA + qb, tp(t, 0)),
                        "v_add_f32 v%d, v%d, v%d" % (self.TLB + qb, self.TLB + qb, tp(t, 1))]
@@ -420,7 +427,7 @@ class Gen(Emitter):
         fixed = {}
         for slot in range(NM):
             last_of_group = slot % self.QB == self.QB - 1
-            cost = 1.0 + (1.0 if slot % self.QB == 0 else 0.0)          # MFMA (+ its s_waitcnt)
+            cost = 1.0 + (1.0 if slot % (self.QB * self.W) == 0 else 0.0)   # MFMA (+ an s_waitcnt)
             if last_of_group:
                 nxt_g = groups[(slot // self.QB + self.PFD) % self.NG]
                 cost += 2.0 if nxt_g[0] == "pv" else 1.0                 # LDS reads issued here
@@ -436,7 +443,7 @@ class Gen(Emitter):
                     lambda g, buf: self.mfma_texts(g, buf, P_prev, S_nxt),
                     lambda g, buf: self.frag_loads(g, buf, kst, vst),
                     self.NF, self.PFD, valu, extra,
-                    lambda i, buf: self.frag_loads(groups[i], buf, nkst, nvst))
+                    lambda i, buf: self.frag_loads(groups[i], buf, nkst, nvst), wait_every=self.W)
         if b == 3:
             self.e("s_branch %s" % L("BODY0_"))
 
@@ -506,10 +513,17 @@ class Gen(Emitter):
         vst = (b + 3) % 4
         pv = [("pv", kc, db) for kc in range(2 * self.SB) for db in range(self.DB)]
         self.e("%s:" % L("EXIT%d_" % b))
-        # the prefetched operands belong to the interleaved order (first half of P V only): same groups
-        self.outstanding = [i for i in range(self.PFD) for _ in range(2)] if "nolds" not in self.exp else []
+        # in flight: the operands of the first PFD groups of the interleaved order.  Its leading P V groups
+        # are the drain's leading groups; reads of K Q^T groups behind them are never used (id -1)
+        lead = min(self.PFD, self.NPVG // 2)
+        groups = self.groups()
+        self.outstanding = []
+        if "nolds" not in self.exp:
+            for i in range(self.PFD):
+                self.outstanding += [i if i < lead else -1] * len(self.frag_loads(groups[i], i % self.NF, 0, vst))
         self.stream(pv, lambda g, buf: self.mfma_texts(g, buf, P_prev, 0),
-                    lambda g, buf: self.frag_loads(g, buf, 0, vst), self.NF, self.PFD, {}, {}, None)
+                    lambda g, buf: self.frag_loads(g, buf, 0, vst), self.NF, self.PFD, {}, {}, None,
+                    prefetched=lead, wait_every=self.W)
         self.e("s_branch %s" % L("DONE_"))
 
     def generate(self):
@@ -545,7 +559,6 @@ class Gen(Emitter):
         # operands of the first PFD groups of iteration 0 ("V(-1)" lives in stage 3)
         self.outstanding = []
         g0 = self.groups()
-        assert all(g[0] == "pv" for g in g0[:self.PFD])
         for i in range(self.PFD):
             self.lds_issue(i, self.frag_loads(g0[i], i % self.NF, 1, 3))
         for b in range(4):
@@ -620,11 +633,13 @@ class Gen(Emitter):
 def main(argv):
     args = list(argv)
     kw = {}
-    while len(args) > 2 and args[-2] in ("--pfd", "--nf", "--drop"):
+    while len(args) > 2 and args[-2] in ("--pfd", "--nf", "--w", "--drop"):
         if args[-2] == "--pfd":
             kw["PFD"] = int(args[-1])
         elif args[-2] == "--nf":
             kw["NF"] = int(args[-1])
+        elif args[-2] == "--w":
+            kw["W"] = int(args[-1])
         else:
             kw["drop"] = tuple(filter(None, args[-1].split(",")))
         args = args[:-2]

@@ -180,8 +180,8 @@ def test_hand_scheduled_sweeps_equal_compiler_scheduled_sweeps(B):
 
 def test_headline_shape_one_head_in_full(B):
     # the forward headline workload's shape (B1 H16 S16384 D128, non-causal) in the launch configuration
-    # `bench.py --config 3 --bwd` times; the oracle computes one head in full (all 16384 rows of dq, dk, dv)
-    cfg, q, k, v, scale = synth.make_config(3)
+    # `bench.py --config 4 --bwd` times; the oracle computes one head in full (all 16384 rows of dq, dk, dv)
+    cfg, q, k, v, scale = synth.make_config(synth.HEADLINE_CONFIG)
     print("bwd", cfg["name"], flush=True)
     d_o = synth.make_do(cfg["B"], cfg["H"], cfg["S_q"], cfg["D"], cfg["seed"])
     got = run_gpu(B, q, k, v, d_o, cfg["causal"], scale)

@@ -92,7 +92,11 @@ def test_memory_capacity_on_the_running_example():
 def _load_generator(name):
     import importlib.util
     import os
-    path = os.path.join(os.path.dirname(ms.__file__), "csrc", name + ".py")
+    import sys
+    csrc = os.path.join(os.path.dirname(ms.__file__), "csrc")
+    if csrc not in sys.path:
+        sys.path.insert(0, csrc)          # the generators import asm_emit from their own directory
+    path = os.path.join(csrc, name + ".py")
     spec = importlib.util.spec_from_file_location(name, path)
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
@@ -108,9 +112,9 @@ def test_register_demand_matches_what_the_generators_allocate():
     assert ranges["QK"][1] - ranges["QK"][0] > I       # S(j+1) is produced while S(j) is still being read
     assert ranges["SM"][1] - ranges["SM"][0] > I       # P(j) is produced while P(j-1) is still being read
     peak = max(ms.live_footprint(g, M, I, ms.GFX950_D128_REGS, ms.GFX950_D128_RESIDENT))
-    gen = _load_generator("gen_attn_loop").Gen(128)
+    gen = _load_generator("gen_attn_loop").Gen("d128")     # the 8-wave tiling: two waves per SIMD
     # the generator double-buffers S and P statically and allocates exactly what the model's values need
-    assert gen.SB - gen.SA == 32 and gen.PB - gen.PA == 16
+    assert gen.SBUF - gen.SA == 32 and gen.PB - gen.PA == 16
     static = 2 * 32 + 2 * 16 + 64 + ms.GFX950_D128_RESIDENT
     assert peak <= static <= 256 and abs(gen.NV - static) <= 8
     # the backward key-owner sweep: accumulators for dK and dV plus the owner's rows do not fit 256,
