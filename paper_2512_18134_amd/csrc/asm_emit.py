@@ -62,7 +62,7 @@ class Emitter:
 
     # ------------------------------------------------------------ MFMA stream
     def stream(self, groups, mfma_texts, frag_loads, NF, PFD, valu_by_slot, extra_by_slot, nxt_frag_loads,
-               prefetched=None, wait_every=1):
+               prefetched=None, wait_every=1, lds_by_slot=None):
         """Emit the slots of one iteration.
 
         groups: fragment groups in issue order; mfma_texts(g, buf) -> the MFMAs fed by group g's fragment
@@ -71,7 +71,9 @@ class Emitter:
         The reads of the first `prefetched` groups (default PFD) are already in flight (ids 0.. in
         self.outstanding); the rest up to PFD is issued first.  wait_every = W: one s_waitcnt per W groups,
         for the operands of all W (needs PFD >= W).  A slot is one MFMA; extras and VALU shares are keyed by
-        slot number.
+        slot number.  lds_by_slot: other LDS reads issued in a slot; they take their place in the in-order
+        count but are never waited for by index (they must retire inside the iteration: a later wait of a
+        fragment covers them).
         """
         n = len(groups)
         prefetched = PFD if prefetched is None else prefetched
@@ -94,11 +96,15 @@ class Emitter:
                         self.lds_issue(j - n + 1000, nxt_frag_loads(j - n, (j - n) % NF))
                 for ins in extra_by_slot.get(slot, []):
                     self.e(ins)
+                for ins in (lds_by_slot or {}).get(slot, []):
+                    self.e(ins)
+                    self.outstanding.append(-1)
                 for ins in valu_by_slot.get(slot, []):
                     self.e(ins)
                 slot += 1
+        assert lds_by_slot is None or -1 not in self.outstanding, "auxiliary LDS reads must retire inside the iteration"
         # the next iteration's prefetches take its own numbering
-        self.outstanding = [x - 1000 for x in self.outstanding]
+        self.outstanding = [x - 1000 if x >= 0 else x for x in self.outstanding]
         assert nxt_frag_loads is None or all(0 <= x < PFD for x in self.outstanding), self.outstanding
         return slot
 

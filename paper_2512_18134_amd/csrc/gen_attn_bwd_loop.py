@@ -28,13 +28,21 @@ Hazards handled by construction (the assembler inserts no wait states):
   * back-to-back MFMAs never share an accumulator (S and dP alternate; the contraction walks its
     2*DB or DB accumulators round robin).
 
+The emitter, the replay of the LDS-read counter and the slot stream are shared with the forward
+generator (asm_emit.py); the tests re-check the hazard rules on the emitted text (asm_emit.check_stream).
+
 usage: gen_attn_bwd_loop.py <kv|q> <D> <out.inc> [bf16|f16]
 """
+import os
 import sys
 
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from asm_emit import Emitter  # noqa: E402
 
-class Gen:
+
+class Gen(Emitter):
     def __init__(self, key_owner, D, NF=4, PFD=3, dtype="bf16", drop=()):
+        Emitter.__init__(self)
         assert D in (64, 128) and dtype in ("bf16", "f16")
         self.KO = key_owner
         # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
@@ -110,30 +118,10 @@ class Gen:
         self.s_ptr1, self.s_ptr2 = 50, 52
         self.s_t2, self.s_t3 = 54, 55
         self.s_m0 = 56            # m0 of the surrounding code (reserved register: saved and restored here)
-        self.lines = []
         # timing experiments only (results are wrong with any of these set): parts of the loop to leave out
         self.exp = set(drop)
 
     # ------------------------------------------------------------------ helpers
-    def e(self, s):
-        self.lines.append(s)
-
-    def lab(self, name):
-        return "%s%%=" % name
-
-    @staticmethod
-    def rg(cls, base, n=1):
-        return "%s%d" % (cls, base) if n == 1 else "%s[%d:%d]" % (cls, base, base + n - 1)
-
-    def vr(self, base, n=1):
-        return self.rg("v", base, n)
-
-    def ar(self, base, n=1):
-        return self.rg("a", base, n)
-
-    def sr(self, base, n=1):
-        return self.rg("s", base, n)
-
     def bufs(self, b):
         """(S_cur, dP_cur, S_nxt, dP_nxt, P_prev, dS_prev, P_new, dS_new) of body b."""
         if b % 2 == 0:
@@ -268,41 +256,17 @@ class Gen:
                 "global_load_lds_dword v%d, %s" % (self.AT, self.sr(self.s_auxbase, 2))]
 
     # ------------------------------------------------------- one MFMA stream
-    def stream(self, grps, bf, rst, tst, valu_by_slot, extra_by_slot, lds_by_slot, prefetched, nxt):
-        NF, PFD = self.NF, self.PFD
-        n = len(grps)
-        def issue(idx, grp, r, t):
-            for ins in self.frag_loads(grp, idx % NF, r, t):
-                if "nolds" not in self.exp:
-                    self.e(ins)
-                self.outstanding.append(idx)
-        for i in range(prefetched, min(PFD, n)):
-            issue(i, grps[i], rst, tst)
-        for i, grp in enumerate(grps):
-            last = max(p for p, x in enumerate(self.outstanding) if x == i)
-            after = len(self.outstanding) - 1 - last
-            if "nolds" not in self.exp:
-                self.e("s_waitcnt lgkmcnt(%d)" % after)
-            self.outstanding = self.outstanding[last + 1:]
-            self.e(self.mfma_text(grp, i % NF, bf))
-            # the fragment buffer of group i+PFD was last read by group i+PFD-NF <= i-1
-            j = i + PFD
-            if j < n:
-                issue(j, grps[j], rst, tst)
-            elif nxt is not None:
-                ng, nr, nt = nxt
-                issue(j - n + 1000, ng[j - n], nr, nt)
-            for ins in extra_by_slot.get(i, []):
-                self.e(ins)
-            for ins in lds_by_slot.get(i, []):      # other LDS reads: counted, never waited for by index
-                if "nolds" not in self.exp:
-                    self.e(ins)
-                self.outstanding.append(-1)
-            for ins in valu_by_slot.get(i, []):
-                self.e(ins)
-        assert -1 not in self.outstanding, "auxiliary LDS reads must retire inside the iteration"
-        self.outstanding = [x - 1000 for x in self.outstanding]
-        assert all(0 <= x < PFD for x in self.outstanding), self.outstanding
+    def run_stream(self, grps, bf, rst, tst, valu_by_slot, extra_by_slot, lds_by_slot, nxt):
+        """One iteration's slots through the shared stream: one MFMA per fragment group."""
+        loads = lambda g, buf, r, t: [] if "nolds" in self.exp else self.frag_loads(g, buf, r, t)
+        nxt_loads = None
+        if nxt is not None:
+            ng, nr, nt = nxt
+            nxt_loads = lambda i, buf: loads(ng[i], buf, nr, nt)
+        if "nolds" in self.exp:
+            lds_by_slot = {}
+        self.stream(grps, lambda g, buf: [self.mfma_text(g, buf, bf)], lambda g, buf: loads(g, buf, rst, tst),
+                    self.NF, self.PFD, valu_by_slot, extra_by_slot, nxt_loads, lds_by_slot=lds_by_slot)
 
     # --------------------------------------------------------------- the loop
     def body(self, b):
@@ -356,7 +320,7 @@ class Gen:
             valu = {}
         if "nodma" in self.exp:
             extra = {2: extra[2]}
-        self.stream(self.groups(), bf, rst, tst, valu, extra, lds, self.PFD, nxt)
+        self.run_stream(self.groups(), bf, rst, tst, valu, extra, lds, nxt)
         if b == NST - 1:
             self.e("s_branch %s" % L("BODY0_"))
 
@@ -385,9 +349,9 @@ class Gen:
         grps = self.chunk_groups(0) + self.chunk_groups(1)
         self.e("%s:" % L("EXIT%d_" % b))
         g0 = self.groups()
-        self.outstanding = [i for i in range(self.PFD) for _ in self.frag_loads(g0[i], 0, 0, 0)]
+        self.outstanding = [] if "nolds" in self.exp else [i for i in range(self.PFD) for _ in self.frag_loads(g0[i], 0, 0, 0)]
         assert grps[:self.PFD] == g0[:self.PFD]
-        self.stream(grps, bf, 0, tst, {}, {}, {}, self.PFD, None)
+        self.run_stream(grps, bf, 0, tst, {}, {}, {}, None)
         self.e("s_branch %s" % L("DONE_"))
 
     def generate(self):
@@ -395,7 +359,7 @@ class Gen:
         e = self.e
         e("s_nop 15")
         e("s_nop 7")
-        e("s_mov_b32 s%d, m0" % self.s_m0)
+        self.save_m0(self.s_m0)
         e("s_mov_b32 s%d, 0" % self.s_j)
         # tiles 0..3 were issued by the prologue: the loop's first load is tile 4 (absolute t_begin + 4)
         e("s_add_i32 s%d, s%d, 4" % (self.s_tk, self.s_tbeg))
@@ -411,9 +375,8 @@ class Gen:
         g0 = self.groups()
         assert all(g[0] == "c" for g in g0[:self.PFD])
         for i in range(self.PFD):
-            for ins in self.frag_loads(g0[i], i % self.NF, 1, self.NST - 1):   # "tile -1" lives in the last stage
-                e(ins)
-                self.outstanding.append(i)
+            if "nolds" not in self.exp:
+                self.lds_issue(i, self.frag_loads(g0[i], i % self.NF, 1, self.NST - 1))   # "tile -1": last stage
         for b in range(self.NST):
             self.body(b)
         for b in range(self.NST):
@@ -422,7 +385,7 @@ class Gen:
             self.drain(b)
         e("%s:" % L("DONE_"))
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
-        e("s_mov_b32 m0, s%d" % self.s_m0)
+        self.restore_m0(self.s_m0)
         e("s_nop 15")
         e("s_nop 7")
 

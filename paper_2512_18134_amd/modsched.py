@@ -383,20 +383,34 @@ def _search(loop, I, L, edges, accept, A=None, blocked=()):
     return rec(0)
 
 
-def joint_schedule(loop, ws, max_len=None, max_interval=None):
+def joint_schedule(loop, ws, max_len=None, max_interval=None, stages=None):
     """The joint problem of Section 4: the smallest I, then the smallest L, over modulo schedules AND warp
     assignments; among equals the assignment that uses the fewest warps.  Returns (M, I, L, A), or None when
-    nothing fits up to max_interval (the paper's Section 5.1 then relaxes the problem)."""
+    nothing fits up to max_interval.
+
+    stages="plain" narrows the search the way Section 5.1 does: at an interval I only schedules that overlap
+    no more copies of the loop body than the best plain modulo schedule at that I (warps ignored) are
+    admitted, i.e. L <= I * ceil(L_plain(I) / I); intervals at which no plain schedule exists are skipped.
+    The joint constraints contain the plain ones, so nothing shorter than L_plain(I) is lost; what is given
+    up are deeper pipelines at a small I, in favour of the next interval.  The default (None) admits them."""
+    assert stages in (None, "plain")
     total = sum(duration(loop, v) for v in loop.rrt)
     max_len = max_len or 2 * total + sum(ws.spillcost.values())
     max_interval = max_interval or max_len
     cands = sorted(_assignments(loop, ws), key=lambda A: len(set(A.values())))
     I = max(res_mii(loop), rec_mii(loop))
     while I <= max_interval:
+        cap = max_len
+        if stages == "plain":
+            plain = optimal_modulo_schedule(loop, I, max_len + I)
+            if plain is None:
+                I += 1
+                continue
+            cap = I * math.ceil(length(loop, plain) / I)
         best = None
         for A in cands:
             edges = warp_edges(loop, A, ws)
-            top = max_len if best is None else best[2] - 1
+            top = cap if best is None else best[2] - 1
             for L in range(1, top + 1):
                 blocked = {v for u, v, _, _ in loop.edges if (u, v) in ws.blocking or A[u] != A[v]}
                 M = _search(loop, I, L, edges, lambda M: is_valid_assignment(loop, M, I, A, ws), A, blocked)
@@ -406,42 +420,6 @@ def joint_schedule(loop, ws, max_len=None, max_interval=None):
         if best is not None:
             return best
         I += 1
-    return None
-
-
-def swp_and_ws(loop, ws, I, L):
-    """One solve of the joint constraint system at a fixed initiation interval and schedule length bound:
-    (M, A) with length(M) <= L, fewest warps first, or None (the paper hands this step to an SMT solver;
-    the graphs here are small enough to enumerate)."""
-    for A in sorted(_assignments(loop, ws), key=lambda A: len(set(A.values()))):
-        edges = warp_edges(loop, A, ws)
-        blocked = {v for u, v, _, _ in loop.edges if (u, v) in ws.blocking or A[u] != A[v]}
-        for length_ in range(1, L + 1):
-            M = _search(loop, I, length_, edges, lambda M: is_valid_assignment(loop, M, I, A, ws), A, blocked)
-            if M is not None:
-                return M, A
-    return None
-
-
-def search_procedure(loop, ws, max_interval=64):
-    """The search of Section 5.1 (its algorithm listing), step for step: for I = 1, 2, ... take the optimal
-    plain modulo schedule M at I (skip I if there is none); starting from L = len(M), try the joint system
-    at (I, L) and lengthen L by one on failure, but only while that keeps the number of overlapped copies
-    ceil(L / I) of the plain schedule; then move on to I + 1.  Returns (M*, I, A*) or None.
-
-    Unlike joint_schedule it never trades a deeper pipeline for a smaller I: a schedule that needs one more
-    overlapped copy than the plain optimum is passed over in favour of the next interval."""
-    total = sum(duration(loop, v) for v in loop.rrt)
-    for I in range(1, max_interval + 1):
-        M = optimal_modulo_schedule(loop, I, 2 * total + I)
-        if M is None:
-            continue
-        L = base = length(loop, M)
-        while math.ceil(L / I) == math.ceil(base / I):
-            got = swp_and_ws(loop, ws, I, L)
-            if got is not None:
-                return got[0], I, got[1]
-            L += 1
     return None
 
 
@@ -460,10 +438,23 @@ def paper_toy():
 
 
 # ------------------------------------------------------------------ the gfx950 loop
-# Measured per-wave costs at D = 128, 64-key tile, 32 query rows per wave, in matrix-pipe cycles:
-# 16 MFMAs of 32 cycles for each product; the softmax of the tile's 32 scores per lane is ~137 VALU
-# instructions, ~790 cycles when one wave issues them alone; LDS operand reads ~200 cycles of the LDS port.
-GFX950_D128 = {"QK": 512, "SM": 790, "PV": 512, "LDS_K": 90, "LDS_V": 115}
+# Per-wave costs of one K/V tile at D = 128 (32 scores per lane), in matrix-pipe cycles.  Sources, all
+# reproducible from the repository (profiles/attn_fwd_d128_config4.md gives the commands):
+#   * an MFMA occupies the matrix pipe for 32 cycles (SQ_VALU_MFMA_BUSY_CYCLES / SQ_INSTS_MFMA), 16 MFMAs
+#     per product;
+#   * on all-zero inputs (chip not power limited) the one-wave-per-SIMD loop keeps the pipe busy 81.5 % of
+#     the cycles while it issues GFX950_STREAM_INSTRS instructions per 32 MFMAs: the wave's issue port is
+#     the binding unit there, at 32 * 32 / 0.815 / 198 = 6.3 cycles per instruction on average;
+#   * the softmax of a tile is GFX950_SOFTMAX_INSTRS of those instructions, the LDS operand reads 16 + 32
+#     (8 + 16 when a fragment feeds two MFMAs).
+GFX950_MFMA_CYCLES = 32
+GFX950_UNTHROTTLED_BUSY = 0.815
+GFX950_STREAM_INSTRS = 198
+GFX950_SOFTMAX_INSTRS = 114
+GFX950_ISSUE_CYCLES = GFX950_MFMA_CYCLES * 32 / GFX950_UNTHROTTLED_BUSY / GFX950_STREAM_INSTRS
+GFX950_D128 = {"QK": 16 * GFX950_MFMA_CYCLES, "SM": round(GFX950_SOFTMAX_INSTRS * GFX950_ISSUE_CYCLES),
+               "PV": 16 * GFX950_MFMA_CYCLES, "LDS_K": round(16 * GFX950_ISSUE_CYCLES),
+               "LDS_V": round(32 * GFX950_ISSUE_CYCLES)}
 
 
 def gfx950_attention(costs=GFX950_D128, U=24):
@@ -486,6 +477,55 @@ def gfx950_attention(costs=GFX950_D128, U=24):
     g.dep("SM", "SM", delta=1)      # running max / row sum
     g.dep("PV", "PV", delta=1)      # accumulator O
     return g, c, F
+
+
+def gfx950_attention_subtiled(costs=GFX950_D128, parts=2, U=24):
+    """The same loop with every tile-level instruction cut into `parts` sub-tiles (Section 6.1: the paper
+    sub-tiles to the size of one matrix instruction before scheduling; here one sub-tile is one 32-row query
+    block of the one-wave-per-SIMD tiling, or one 32-key block of the two-wave one).  Sub-tile p of the
+    softmax needs only sub-tile p of the scores, sub-tile p of the second product only sub-tile p of P."""
+    unit = {"QK": "MFMA", "SM": "VALU", "PV": "MFMA"}
+    names = [n + str(p) for p in range(parts) for n in ("QK", "SM", "PV")]
+    Cn, F = normalise_costs([costs[n[:2]] / parts for n in names], U)
+    c = dict(zip(names, Cn))
+    g = Loop({"MFMA": 1, "VALU": 1})
+    for n in names:
+        g.op(n, unit[n[:2]], c[n])
+    for p in range(parts):
+        g.dep("QK%d" % p, "SM%d" % p)
+        g.dep("SM%d" % p, "PV%d" % p)
+        g.dep("SM%d" % p, "SM%d" % p, delta=1)      # row state
+        g.dep("PV%d" % p, "PV%d" % p, delta=1)      # accumulator O
+    return g, c, F
+
+
+def stream_mix(lines, body=1):
+    """Instruction mix of one steady-state iteration of a generated loop (the text between the labels of
+    body `body` and the next one): {class: count} with classes mfma, valu (transcendentals included),
+    lds, vmem, wait, salu (s_nop and barrier included)."""
+    lines = [l.strip() for l in lines]
+    i = next(k for k, l in enumerate(lines) if l.startswith("BODY%d_" % body))
+    j = next(k for k, l in enumerate(lines) if l.startswith("BODY%d_" % (body + 1)))
+    mix = {"mfma": 0, "valu": 0, "lds": 0, "vmem": 0, "wait": 0, "salu": 0}
+    for l in lines[i + 1:j]:
+        if l.endswith(":"):
+            continue
+        op = l.split()[0]
+        key = ("mfma" if op.startswith("v_mfma") else "valu" if op.startswith("v_") else "lds" if op.startswith("ds_")
+               else "vmem" if op.startswith("global_") else "wait" if op.startswith("s_waitcnt") else "salu")
+        mix[key] += 1
+    return mix
+
+
+def slot_level_bounds(mix, waves_per_simd):
+    """Lower bounds on the initiation interval of one iteration at the granularity of single instructions
+    (cycles per SIMD): the matrix pipe needs GFX950_MFMA_CYCLES per MFMA of every wave on the SIMD; a wave's
+    issue port needs GFX950_ISSUE_CYCLES per instruction of that wave (waves issue side by side).  The
+    generated loops issue exactly one MFMA per slot, so their I in slots is mix['mfma']: the matrix-pipe bound."""
+    matrix = mix["mfma"] * GFX950_MFMA_CYCLES * waves_per_simd
+    issue = sum(mix.values()) * GFX950_ISSUE_CYCLES
+    return {"matrix": matrix, "issue": issue, "interval": max(matrix, issue),
+            "matrix_busy": matrix / max(matrix, issue)}
 
 
 # Registers per lane of the values in that graph (D = 128, 32 query rows per wave, 64-key tile): the

@@ -17,6 +17,7 @@ CSRC = os.path.join(ROOT, "paper_2512_18134_amd", "csrc")
 sys.path.insert(0, CSRC)
 
 import asm_emit  # noqa: E402
+import gen_attn_bwd_loop  # noqa: E402
 import gen_attn_loop  # noqa: E402
 
 FWD = [(name, dt) for name in gen_attn_loop.CONFIGS for dt in ("bf16", "f16")]
@@ -51,6 +52,24 @@ def test_forward_out_of_line_sections(name, b):
         assert asm_emit.check_stream(path) == len(path)
         if "EXIT%d_" % b in detour:
             assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
+
+
+BWD = [(ko, d, dt) for ko in (True, False) for d in (64, 128) for dt in ("bf16", "f16")]
+
+
+@pytest.mark.parametrize("key_owner,d,dtype", BWD)
+def test_backward_sweeps(key_owner, d, dtype):
+    g = gen_attn_bwd_loop.Gen(key_owner, d, dtype=dtype)
+    g.generate()
+    lines = [l.replace("%=", "") for l in g.lines]
+    path = asm_emit.walk(lines, loop_label="BODY0_", loop_visits=2)
+    assert sum(1 for l in path if l.startswith("v_mfma")) == 2 * g.NST * g.NM
+    assert asm_emit.check_stream(path) == len(path)
+    for b in range(g.NST):
+        for detour in (["MASKLO%d_" % b], ["MASKHI%d_" % b], ["SLOW%d_" % b], ["MASKLO%d_" % b, "MASKHI%d_" % b, "SLOW%d_" % b],
+                       ["EXIT%d_" % b]):
+            path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=2)
+            assert asm_emit.check_stream(path) == len(path)
 
 
 def test_checker_catches_planted_mistakes():
