@@ -42,7 +42,7 @@ extern "C" {
  *   causal, scale, stream   as in attn_fwd; they must be the values the forward call used
  *
  * Ownership: the caller owns all ten buffers and keeps them alive until the work
- * enqueued on `stream` has completed.  The library allocates nothing and keeps no state.
+ * enqueued on `stream` has completed.  The library allocates nothing and keeps no state that changes a result.
  * Outputs and the workspace must not overlap the inputs or each other.
  *
  * Errors: as attn_fwd -- arguments are validated on the host before any HIP call, a

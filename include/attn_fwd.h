@@ -4,10 +4,10 @@
  * The operation is the per-SM loop of the paper's Section 3 running example
  * (Fig. 1a; its software-pipelined form is Fig. 1f):
  *     O = 0;  for each K/V tile i:  S = gemm(Q, K[i]);  P = exp(S);  O += gemm(P, V[i])
- * in its complete online-softmax form, i.e. with the running row maximum,
- * the accumulator rescale and the final normalisation that Section 6.2 calls
- * "softmax calculations" and "accumulator rescaling", plus the log-sum-exp of
- * every row.  For b in [0,B), h in [0,H), i in [0,S_q):
+ * in its complete online-softmax form, i.e. with the max subtraction, the
+ * accumulator rescale and the final normalisation that the figure leaves out
+ * and Section 6.2 counts among the loop's work, plus the log-sum-exp of every
+ * row.  For b in [0,B), h in [0,H), i in [0,S_q):
  *
  *     J(i)   = { j : 0 <= j < S_kv }                  causal == 0
  *            = { j : 0 <= j < S_kv, j <= i }          causal != 0 (top-left aligned)
@@ -56,7 +56,8 @@ typedef enum attn_status {
  *
  * Ownership: the caller owns all five buffers and keeps them alive until the
  * work enqueued on `stream` has completed.  The library allocates nothing,
- * keeps no state between calls and never synchronises the device.  o/lse must
+ * keeps no state between calls that changes a result (it remembers only that a
+ * kernel's launch attribute has been set) and never synchronises the device.  o/lse must
  * not overlap q/k/v.
  *
  * Errors: arguments are validated on the host before any HIP call; on a
