@@ -40,9 +40,15 @@ alpha = exp2(c (m_old - m_new)) and recomputes the tile's P from its scores,
 which the fast path leaves intact (the exponent arguments go to temporaries).
 On N(0,1) inputs this pass runs once per workgroup.
 
-Rare events share one test per iteration: j >= s_special (loop exit, tiles that
+Rare events share one test per iteration: j >= s_special (last tile, tiles that
 need a mask, tiles whose loads reach past S_kv) branches out of line and comes
 back with SCC set, which the two load slots test again.
+
+The ramp of the schedule is peeled, so no MFMA runs on operands that do not
+exist: the first iteration holds K(1) Q^T and softmax(S(0)) only (there is no
+P(-1) V(-1)), and the last tile has a body of its own per ring phase:
+P(n-2) V(n-2) beside softmax(S(n-1)), then P(n-1) V(n-1), no K Q^T, no loads.
+A launch with one tile leaves after the first iteration through P(0) V(0).
 
 The compiler cannot be made to hold this schedule (it spills), so registers are
 assigned here and the loop is emitted as ONE inline-asm statement with operands
@@ -160,7 +166,8 @@ class Gen(Emitter):
         self.s_kptr, self.s_vptr = 46, 48
         self.s_t2 = 50
         self.s_m0 = 51            # m0 of the surrounding code (reserved register: saved and restored here)
-        self.s_lk = 52            # LDS addresses of this wave's K loads, [stage][i]
+        self.s_nm1 = 52           # index of the last tile
+        self.s_lk = 53            # LDS addresses of this wave's K loads, [stage][i]
         self.s_lv = self.s_lk + 4 * self.NLD
         self.s_last = self.s_lv + 4 * self.NLD - 1
         assert self.s_last < 100
@@ -275,17 +282,17 @@ class Gen(Emitter):
             ops.append("v_add_f32 v%d, v%d, v%d" % (self.TS, self.TLA, self.TLA + 1))
         return ops
 
-    def check_ops(self, b):
+    def check_ops(self, tag):
         """Tile row sums below the bound?  Otherwise (too large, inf or NaN) take the out-of-line pass."""
         if "novalu" in self.exp:
             return []
         ts = self.TS if self.QB == 2 else self.TLA
         ops = ["v_cmp_ngt_f32 vcc, s%d, v%d" % (self.s_tau, ts),     # not (bound > sum)
-               "s_cbranch_vccnz %s" % self.lab("SLOW%d_" % b),
-               "%s:" % self.lab("SLOWRET%d_" % b)]
+               "s_cbranch_vccnz %s" % self.lab("SLOW%s_" % tag),
+               "%s:" % self.lab("SLOWRET%s_" % tag)]
         if "sgprcheck" in self.exp:
             ops = ["v_cmp_ngt_f32 s[96:97], s%d, v%d" % (self.s_tau, ts), "s_cmp_lg_u64 s[96:97], 0",
-                   "s_cbranch_scc1 %s" % self.lab("SLOW%d_" % b), "%s:" % self.lab("SLOWRET%d_" % b)]
+                   "s_cbranch_scc1 %s" % self.lab("SLOW%s_" % tag), "%s:" % self.lab("SLOWRET%s_" % tag)]
         for qb in range(self.QB):
             ops.append("v_add_f32 v%d, v%d, v%d" % (self.L + qb, self.L + qb, self.TLA + qb))
         return ops
@@ -390,92 +397,145 @@ class Gen(Emitter):
             self.e("global_load_lds_dwordx4 v%d, %s" % (t, self.sr(base, 2)))
 
     # --------------------------------------------------------------- the loop
-    def body(self, b):
-        NM = self.NM
+    def entry_reads(self, vst, pv_only):
+        """State of the LDS queue where an iteration starts: the iteration before it (or the set-up code) has
+        issued the reads of the first PFD groups of the interleaved order.  A P V-only iteration uses the
+        leading P V groups among them; the K Q^T reads behind those are never used (id -1)."""
+        groups = self.groups()
+        lead = min(self.PFD, self.NPVG // 2) if pv_only else self.PFD
+        self.outstanding = []
+        for i in range(self.PFD):
+            self.outstanding += [i if i < lead else -1] * len(self.frag_loads(groups[i], i % self.NF, 0, vst))
+        return lead
+
+    def body(self, b, kind="loop"):
+        """One iteration, for ring phase b (iteration j = b mod 4).
+        kind "loop":  P(j-1)V(j-1) and K(j+1)Q^T around softmax(S(j)), loads of K(j+4), V(j+2).
+        kind "first": iteration 0 (b = 0): there is no P(-1): K(1)Q^T and softmax(S(0)) only.
+        kind "last":  iteration n-1 (n > 1): there is no tile n: P(n-2)V(n-2) next to softmax(S(n-1)), then
+                      P(n-1)V(n-1), and the loop is done; no loads."""
+        tag = {"loop": "%d" % b, "first": "F", "last": "L%d" % b}[kind]
         S_cur, S_nxt, P_prev, P_new = self.bufs(b)
         kst, vst = (b + 1) % 4, (b + 3) % 4           # stages of K(j+1), V(j-1)
         nb = (b + 1) % 4
         nkst, nvst = (nb + 1) % 4, (nb + 3) % 4
-        groups = self.groups()
+        all_groups = self.groups()
+        pv = [g for g in all_groups if g[0] == "pv"]
+        qk = [g for g in all_groups if g[0] == "qk"]
+        # the groups next to the softmax of S(j), and the groups after it
+        groups = {"loop": all_groups, "first": qk, "last": [("a",) + g for g in pv]}[kind]
+        tail = [("b",) + g for g in pv] if kind == "last" else []
+        n_soft = len(groups) * self.QB                 # slots that carry the softmax
         L = self.lab
-        self.e("%s:" % L("BODY%d_" % b))
-        # one test for everything rare: loop exit, masked tiles, loads that reach past S_kv
-        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))
-        self.e("s_cbranch_scc1 %s" % L("SPECIAL%d_" % b))
-        self.e("%s:" % L("TOP%d_" % b))               # SCC: this is a special iteration (kept up to the load slots)
+        if kind != "last":
+            self.e("%s:" % L({"loop": "BODY%d_" % b, "first": "FIRST_"}[kind]))
+            # one test for everything rare: last iteration, masked tiles, loads that reach past S_kv
+            self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))
+            self.e("s_cbranch_scc1 %s" % L("SPECIAL%s_" % tag))
+        self.e("%s:" % L("TOP%s_" % tag))              # SCC: this is a special iteration (kept up to the load slots)
         # loads of the previous iteration may stay in flight; everything older has landed
         if "nobar" not in self.exp:
-            self.e("s_waitcnt vmcnt(%d)" % (2 * self.NLD))
+            self.e("s_waitcnt vmcnt(%d)" % (0 if kind == "last" else 2 * self.NLD))
             self.e("s_barrier")
         # ---- scalar work of the slots: K(j+4) -> K stage b in slot 0, V(j+2) -> V stage (b+2)%4 in slot 1
         # (nothing between the test above and these two branches writes SCC), pointer bumps in slot 2
         extra = {}
-        extra[0] = ["s_cbranch_scc1 %s" % L("KSLOW%d_" % b)] + self.dma_fast("k", b) + ["%s:" % L("KRET%d_" % b)]
-        extra[1] = ["s_cbranch_scc1 %s" % L("VSLOW%d_" % b)] + self.dma_fast("v", (b + 2) % 4) + ["%s:" % L("VRET%d_" % b)]
-        extra[2] = [
-            "s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kptr, self.TB),
-            "s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kptr + 1),
-            "s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vptr, self.TB),
-            "s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vptr + 1),
-            "s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j)]
-        if "nodma" in self.exp:
-            extra[0], extra[1] = [], []
+        if kind != "last":
+            extra[0] = ["s_cbranch_scc1 %s" % L("KSLOW%s_" % tag)] + self.dma_fast("k", b) + ["%s:" % L("KRET%s_" % tag)]
+            extra[1] = ["s_cbranch_scc1 %s" % L("VSLOW%s_" % tag)] + self.dma_fast("v", (b + 2) % 4) + ["%s:" % L("VRET%s_" % tag)]
+            extra[2] = [
+                "s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kptr, self.TB),
+                "s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kptr + 1),
+                "s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vptr, self.TB),
+                "s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vptr + 1),
+                "s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j)]
+            if "nodma" in self.exp:
+                extra[0], extra[1] = [], []
         # ---- VALU program: dealt out so that every slot carries about the same issue cost
         b_ops = self.pair_ops(S_cur, P_new)
-        c_ops = self.combine_ops(S_nxt)
-        nc = 4 if c_ops else 0                        # slots reserved at the end for the combine
+        # sum of the K Q^T partial accumulators: in the last slots of a loop iteration (its K Q^T ends in the
+        # middle); after the first iteration, whose K Q^T fills every slot
+        c_ops = self.combine_ops(S_nxt) if kind != "last" else []
+        nc = 4 if c_ops and kind == "loop" else 0
         fixed = {}
-        for slot in range(NM):
+        for slot in range(n_soft):
             last_of_group = slot % self.QB == self.QB - 1
             cost = 1.0 + (1.0 if slot % (self.QB * self.W) == 0 else 0.0)   # MFMA (+ an s_waitcnt)
             if last_of_group:
-                nxt_g = groups[(slot // self.QB + self.PFD) % self.NG]
-                cost += 2.0 if nxt_g[0] == "pv" else 1.0                 # LDS reads issued here
+                nxt_g = (groups + tail + all_groups)[slot // self.QB + self.PFD]
+                cost += 2.0 if "pv" in nxt_g else 1.0                    # LDS reads issued here
             cost += len([x for x in extra.get(slot, []) if not x.endswith(":")])
             fixed[slot] = cost
-        valu = spread(b_ops, fixed, NM - nc)
+        valu = spread(b_ops, fixed, n_soft - nc)
         for i in range(nc):
-            valu[NM - nc + i] = c_ops[i * len(c_ops) // nc:(i + 1) * len(c_ops) // nc]
+            valu[n_soft - nc + i] = c_ops[i * len(c_ops) // nc:(i + 1) * len(c_ops) // nc]
         # the last K Q^T MFMA must be >= 11 wait states before the combine
-        assert not c_ops or (self.NPVG // 2 + self.NQKG) * self.QB <= NM - nc - 3
-        valu[NM - 1] = valu.get(NM - 1, []) + self.check_ops(b)     # the row-sum test closes the last slot
+        assert nc == 0 or (self.NPVG // 2 + self.NQKG) * self.QB <= n_soft - nc - 3
+        valu[n_soft - 1] = valu.get(n_soft - 1, []) + self.check_ops(tag)   # the row-sum test closes the softmax
+        if kind == "last":
+            # reads in flight: the previous iteration's prefetches.  V(n-1) lies in V stage b
+            lead = self.entry_reads(vst, pv_only=True)
+            self.stream(groups + tail,
+                        lambda g, buf: self.mfma_texts(g[1:], buf, P_prev if g[0] == "a" else P_new, 0),
+                        lambda g, buf: self.frag_loads(g[1:], buf, 0, vst if g[0] == "a" else b % 4),
+                        self.NF, self.PFD, valu, extra, None, prefetched=lead, wait_every=self.W)
+            self.e("s_branch %s" % L("DONE_"))
+            return
+        if kind == "first":
+            self.outstanding = []
+        else:
+            self.entry_reads(vst, pv_only=False)
         self.stream(groups,
                     lambda g, buf: self.mfma_texts(g, buf, P_prev, S_nxt),
                     lambda g, buf: self.frag_loads(g, buf, kst, vst),
                     self.NF, self.PFD, valu, extra,
-                    lambda i, buf: self.frag_loads(groups[i], buf, nkst, nvst), wait_every=self.W)
-        if b == 3:
+                    lambda i, buf: self.frag_loads(all_groups[i], buf, nkst, nvst),
+                    prefetched=0 if kind == "first" else None, wait_every=self.W)
+        if kind == "first":
+            if c_ops:
+                self.e("s_nop 15")
+                for ins in c_ops:
+                    self.e(ins)
+            self.e("s_branch %s" % L("BODY1_"))
+        elif b == 3:
             self.e("s_branch %s" % L("BODY0_"))
 
-    def out_of_line(self, b):
+    def out_of_line(self, b, kind="loop"):
         L = self.lab
+        tag = {"loop": "%d" % b, "first": "F", "last": "L%d" % b}[kind]
         S_cur, S_nxt, P_prev, P_new = self.bufs(b)
         QB = self.QB
-        # ---- rare iterations: past the last tile?  a tile that needs a mask?  (its loads: KSLOW / VSLOW)
-        self.e("%s:" % L("SPECIAL%d_" % b))
-        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_ntiles))
-        self.e("s_cbranch_scc1 %s" % L("EXIT%d_" % b))
-        self.e("s_cmp_lt_i32 s%d, s%d" % (self.s_j, self.s_jmask))
-        self.e("s_cbranch_scc1 %s" % L("NOMASK%d_" % b))
-        # mask pre-pass: keys past the causal diagonal / past S_kv become -inf
-        self.e("s_lshl_b32 s%d, s%d, %d" % (self.s_t2, self.s_j, {32: 5, 64: 6}[self.BN]))
-        self.e("v_mov_b32 v%d, 0xff800000" % self.NEGINF)
-        for qb in range(QB):
-            self.e("v_subrev_u32 v%d, s%d, v%d" % (self.THR + qb, self.s_t2, self.THRB + qb))  # limit - 4g - BN j
-        for qb in range(QB):
-            for sb in range(self.SB):
-                for r in range(16):
-                    const = 32 * sb + 8 * (r >> 2) + (r & 3)
-                    x = self.s_reg(S_cur, qb, sb, 0, r)
-                    self.e("v_cmp_gt_i32 vcc, %d, v%d" % (const, self.THR + qb))       # key index > limit ?
-                    self.e("v_cndmask_b32 v%d, v%d, v%d, vcc" % (x, x, self.NEGINF))
-        self.e("%s:" % L("NOMASK%d_" % b))
-        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))                    # SCC = 1 again
-        self.e("s_branch %s" % L("TOP%d_" % b))
+        if kind != "last":
+            # ---- rare iterations: past the last tile (only ever seen by BODY1, when there is a single
+            # tile)?  a tile that needs a mask?  the last tile?  (its loads: KSLOW / VSLOW)
+            self.e("%s:" % L("SPECIAL%s_" % tag))
+            if kind == "loop" and b == 1:
+                self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_ntiles))
+                self.e("s_cbranch_scc1 %s" % L("EXIT1_"))
+            self.e("s_cmp_lt_i32 s%d, s%d" % (self.s_j, self.s_jmask))
+            self.e("s_cbranch_scc1 %s" % L("NOMASK%s_" % tag))
+            # mask pre-pass: keys past the causal diagonal / past S_kv become -inf
+            self.e("s_lshl_b32 s%d, s%d, %d" % (self.s_t2, self.s_j, {32: 5, 64: 6}[self.BN]))
+            self.e("v_mov_b32 v%d, 0xff800000" % self.NEGINF)
+            for qb in range(QB):
+                self.e("v_subrev_u32 v%d, s%d, v%d" % (self.THR + qb, self.s_t2, self.THRB + qb))  # limit - 4g - BN j
+            for qb in range(QB):
+                for sb in range(self.SB):
+                    for r in range(16):
+                        const = 32 * sb + 8 * (r >> 2) + (r & 3)
+                        x = self.s_reg(S_cur, qb, sb, 0, r)
+                        self.e("v_cmp_gt_i32 vcc, %d, v%d" % (const, self.THR + qb))       # key index > limit ?
+                        self.e("v_cndmask_b32 v%d, v%d, v%d, vcc" % (x, x, self.NEGINF))
+            self.e("%s:" % L("NOMASK%s_" % tag))
+            if kind == "loop":
+                self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_nm1))                   # the last tile?
+                self.e("s_cbranch_scc1 %s" % L("TOPL%d_" % b))
+            self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))                    # SCC = 1 again
+            self.e("s_branch %s" % L("TOP%s_" % tag))
         # ---- a tile row sum failed the test: exact row maxima of the (intact) scores, move the references
         # there (alpha = exp2((m_ref - m_new) c); 0 when m_ref was still -inf), redo the tile's P, and scale
-        # the accumulators (every MFMA of the iteration has been issued; wait for the last to retire)
-        self.e("%s:" % L("SLOW%d_" % b))
+        # the accumulators (every MFMA that uses the old reference has been issued; wait for the last to retire)
+        self.e("%s:" % L("SLOW%s_" % tag))
         for ins in self.max_ops(S_cur) + self.pairmax_ops():
             self.e(ins)
         for qb in range(QB):
@@ -489,38 +549,36 @@ class Gen(Emitter):
             self.e("v_mul_f32 v%d, v%d, v%d" % (self.L + qb, self.L + qb, self.ALPHA + qb))
         for ins in self.pair_ops(S_cur, P_new):
             self.e(ins)
-        self.e("s_nop 15")
-        for ins in self.rescale_o_ops():
-            self.e(ins)
-        self.e("s_nop 7")
-        self.e("s_branch %s" % L("SLOWRET%d_" % b))
+        if kind == "first":      # nothing has been accumulated yet
+            self.e("s_nop 1")
+        else:
+            self.e("s_nop 15")
+            for ins in self.rescale_o_ops():
+                self.e(ins)
+            self.e("s_nop 7")
+        self.e("s_branch %s" % L("SLOWRET%s_" % tag))
+        if kind == "last":
+            return
         # ---- ragged-tile loads
-        self.e("%s:" % L("KSLOW%d_" % b))
+        self.e("%s:" % L("KSLOW%s_" % tag))
         if "nodma" not in self.exp:
             self.dma_slow("k", b, 4)
         self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))                    # SCC = 1 for the V slot
-        self.e("s_branch %s" % L("KRET%d_" % b))
-        self.e("%s:" % L("VSLOW%d_" % b))
+        self.e("s_branch %s" % L("KRET%s_" % tag))
+        self.e("%s:" % L("VSLOW%s_" % tag))
         if "nodma" not in self.exp:
             self.dma_slow("v", (b + 2) % 4, 2)
-        self.e("s_branch %s" % L("VRET%d_" % b))
+        self.e("s_branch %s" % L("VRET%s_" % tag))
 
     def drain(self, b):
-        """Loop exit taken at the top of iteration b: O += P(n-1) V(n-1); the operands of the first PFD
-        groups were prefetched by the previous iteration."""
+        """Loop exit at the top of iteration b (b = 1: a launch with a single tile, whose only iteration was
+        the first one): O += P(0) V(0); the operands of the first PFD groups were prefetched by that iteration."""
         L = self.lab
         S_cur, S_nxt, P_prev, P_new = self.bufs(b)
         vst = (b + 3) % 4
         pv = [("pv", kc, db) for kc in range(2 * self.SB) for db in range(self.DB)]
         self.e("%s:" % L("EXIT%d_" % b))
-        # in flight: the operands of the first PFD groups of the interleaved order.  Its leading P V groups
-        # are the drain's leading groups; reads of K Q^T groups behind them are never used (id -1)
-        lead = min(self.PFD, self.NPVG // 2)
-        groups = self.groups()
-        self.outstanding = []
-        if "nolds" not in self.exp:
-            for i in range(self.PFD):
-                self.outstanding += [i if i < lead else -1] * len(self.frag_loads(groups[i], i % self.NF, 0, vst))
+        lead = self.entry_reads(vst, pv_only=True)
         self.stream(pv, lambda g, buf: self.mfma_texts(g, buf, P_prev, 0),
                     lambda g, buf: self.frag_loads(g, buf, 0, vst), self.NF, self.PFD, {}, {}, None,
                     prefetched=lead, wait_every=self.W)
@@ -536,10 +594,11 @@ class Gen(Emitter):
         e("s_mov_b32 s%d, 0" % self.s_j)
         e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, self.tau_bits()))   # bound on a tile's row sum
         # first iteration that is not plain: min(first masked tile, first tile whose K load (4 tiles ahead)
-        # reaches past S_kv, n_tiles)
+        # reaches past S_kv, last tile)
+        e("s_sub_i32 s%d, s%d, 1" % (self.s_nm1, self.s_ntiles))
         e("s_sub_i32 s%d, s%d, 4" % (self.s_special, self.s_tfull))
         e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_jmask))
-        e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_ntiles))
+        e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_nm1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kbase, 4 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kbase + 1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vbase, 2 * self.TB))
@@ -549,24 +608,21 @@ class Gen(Emitter):
                 off = st * self.TB + i * self.NW * 1024
                 e("s_add_u32 s%d, s%d, %d" % (self.s_lk + st * self.NLD + i, self.s_ldsk, off))
                 e("s_add_u32 s%d, s%d, %d" % (self.s_lv + st * self.NLD + i, self.s_ldsv, off))
-        for i in range(8 * QB * self.SB):
-            e("v_mov_b32 v%d, 0" % (self.PA + i))                    # P(-1) = 0
         for qb in range(QB):
             e("v_mov_b32 v%d, 0xff800000" % (self.MREF + qb))        # no reference yet: the first tile's test fails
             e("v_mov_b32 v%d, 0xff800000" % (self.MRC + qb))
             e("v_mov_b32 v%d, 0" % (self.L + qb))
-            e("v_mov_b32 v%d, 1.0" % (self.ALPHA + qb))
-        # operands of the first PFD groups of iteration 0 ("V(-1)" lives in stage 3)
-        self.outstanding = []
-        g0 = self.groups()
-        for i in range(self.PFD):
-            self.lds_issue(i, self.frag_loads(g0[i], i % self.NF, 1, 3))
+        self.body(0, "first")
         for b in range(4):
             self.body(b)
         for b in range(4):
+            self.body(b, "last")
+        self.out_of_line(0, "first")
+        for b in range(4):
             self.out_of_line(b)
         for b in range(4):
-            self.drain(b)
+            self.out_of_line(b, "last")
+        self.drain(1)
         e("%s:" % L("DONE_"))
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
         self.restore_m0(self.s_m0)

@@ -3,8 +3,9 @@ hardware does not enforce, checked on the emitted text itself (asm_emit.check_st
 by an LDS read is covered by an s_waitcnt before its first use, MFMA results are not touched by the VALU
 within 11 wait states, VALU results not read by an MFMA within 2, transcendental results not used by the
 next instruction, one wait state between a scalar write of m0 and a direct global->LDS load.  The main path
-is walked twice round the four loop bodies (loop-carried distances), and once through every out-of-line
-section (mask pre-pass, exact-maximum pass, ragged loads, each loop exit).  Also: the library build's
+is walked through the first iteration and twice round the four loop bodies (loop-carried distances), and
+once through every out-of-line section (mask pre-pass, exact-maximum pass, ragged loads, the last iteration
+of each ring phase, the single-tile exit).  Also: the library build's
 generated files are exactly what the generators emit, with or without stray environment variables."""
 import os
 import subprocess
@@ -35,7 +36,8 @@ def test_forward_main_path_twice_round(name, dtype):
     path = asm_emit.walk(lines, loop_label="BODY0_", loop_visits=2)
     n_mfma = sum(1 for l in path if l.startswith("v_mfma"))
     g = gen_attn_loop.Gen(name)
-    assert n_mfma == 2 * 4 * g.NM                      # two full rounds of the four bodies
+    # the first iteration (K Q^T only), bodies 1..3, then two full rounds of the four bodies
+    assert n_mfma == g.NQKG * g.QB + 11 * g.NM
     assert asm_emit.check_stream(path) == len(path)
 
 
@@ -43,15 +45,38 @@ def test_forward_main_path_twice_round(name, dtype):
 @pytest.mark.parametrize("b", range(4))
 def test_forward_out_of_line_sections(name, b):
     lines = fwd_lines(name)
+    g = gen_attn_loop.Gen(name)
     # each detour is taken the first time its branch is met (body b of the first round; the bodies are
     # alike, so b = 1..3 also cover a detour with loop-carried state before it), then the loop goes on
     for detour in (["SLOW%d_" % b], ["SPECIAL%d_" % b, "KSLOW%d_" % b, "VSLOW%d_" % b],
-                   ["SPECIAL%d_" % b, "NOMASK%d_" % b, "KSLOW%d_" % b, "VSLOW%d_" % b],
-                   ["SPECIAL%d_" % b, "EXIT%d_" % b]):
+                   ["SPECIAL%d_" % b, "NOMASK%d_" % b, "KSLOW%d_" % b, "VSLOW%d_" % b]):
         path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=2)
         assert asm_emit.check_stream(path) == len(path)
-        if "EXIT%d_" % b in detour:
-            assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
+        assert sum(1 for l in path if l.startswith("v_mfma")) == g.NQKG * g.QB + 11 * g.NM
+    # the last iteration (with and without the mask pre-pass and the exact-maximum pass) ends the loop:
+    # P V of the tile before, then P V of the last tile
+    for detour in (["SPECIAL%d_" % b, "TOPL%d_" % b], ["SPECIAL%d_" % b, "NOMASK%d_" % b, "TOPL%d_" % b],
+                   ["SPECIAL%d_" % b, "TOPL%d_" % b, "SLOWL%d_" % b]):
+        path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=2)
+        assert asm_emit.check_stream(path) == len(path)
+        assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
+        tail = [l for l in path if l.startswith("v_mfma")][-2 * g.NPVG * g.QB:]
+        after = path[max(k for k, l in enumerate(path) if l == "s_barrier"):]
+        assert all(", 0" not in l for l in tail) and not any(l.startswith("global_load_lds") for l in after)
+
+
+@pytest.mark.parametrize("name", list(gen_attn_loop.CONFIGS))
+def test_forward_first_iteration_and_single_tile(name):
+    lines = fwd_lines(name)
+    g = gen_attn_loop.Gen(name)
+    for detour in (["SLOWF_"], ["SPECIALF_", "KSLOWF_", "VSLOWF_"], ["SPECIALF_", "NOMASKF_", "KSLOWF_", "VSLOWF_"]):
+        path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=1)
+        assert asm_emit.check_stream(path) == len(path)
+    # a launch with one tile: the first iteration (its loads clamped), then straight to P(0) V(0)
+    path = asm_emit.walk(lines, take=["SPECIALF_", "SLOWF_", "KSLOWF_", "VSLOWF_", "SPECIAL1_", "EXIT1_"])
+    assert asm_emit.check_stream(path) == len(path)
+    assert sum(1 for l in path if l.startswith("v_mfma")) == (g.NQKG + g.NPVG) * g.QB
+    assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
 
 
 BWD = [(ko, d, dt) for ko in (True, False) for d in (64, 128) for dt in ("bf16", "f16")]
