@@ -6,6 +6,7 @@
     python bench.py --config 4 --inputs zeros           # same launch on all-zero tensors (power-limit evidence)
     python bench.py --paper-seq 16384 [--dtype f16]     # the paper's own sweep shape (Section 6.2)
     python bench.py --probe-mfma                        # matrix-pipe ceiling: MFMA-only loop of the debug build
+    python bench.py --probe-dq-atomics                  # cost of a single-pass backward's atomic dQ reduction alone
 
 A "step" is one attn_fwd call (the whole hot path) over one batch of seeded
 synthetic Q/K/V that is already resident in HBM.  Prints ONE JSON line.
@@ -172,6 +173,39 @@ def probe_mfma(args, dev):
                       "iters": iters, "results": res}), flush=True)
 
 
+def probe_dq_atomics(args, dev):
+    """What the fp32 atomic reduction of dQ in a single-pass backward (the paper's Section 6.3 form) costs alone:
+    attn_probe_dq_atomics of the debug build on the paper's shape (B4 H32 D128), every (128-key tile, 64-query
+    tile) pair adding a 64 x 128 fp32 block.  Prints one JSON line."""
+    import ctypes
+    import torch
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2512_18134_amd", "libmi355attn_debug.so"))
+    lib.attn_probe_dq_atomics.restype = ctypes.c_int
+    lib.attn_probe_dq_atomics.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+    stream = torch.cuda.current_stream(dev)
+    res = {}
+    for S in (2048, 4096, 8192):
+        for causal in (0, 1):
+            dq = torch.zeros((128, S, 128), dtype=torch.float32, device=dev)
+            call = lambda: lib.attn_probe_dq_atomics(dq.data_ptr(), 128, S, S, causal, stream.cuda_stream)
+            assert call() == 0
+            torch.cuda.synchronize()
+            rows = torch.arange(S, device=dev)
+            want = (rows // 64 // 2 + 1 if causal else torch.full((S,), S // 128, device=dev)).to(torch.float32)
+            assert torch.equal(dq, want[None, :, None].expand_as(dq)), "atomic sums are wrong"
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+            for e0, e1 in evs:
+                e0.record(stream)
+                call()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+            nbytes = float(want.sum().item()) * 128 * 128 * 4
+            res["S%d_%s" % (S, "causal" if causal else "full")] = {"ms": ms, "atomic_GB": nbytes / 1e9,
+                                                                   "TB_per_s": nbytes / ms / 1e9}
+    print(json.dumps({"probe": "fp32 atomic dQ reduction of a single-pass backward, B4 H32 D128", "results": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,6 +218,8 @@ def main():
                          "bits: what the schedule sustains when the chip is not power limited)")
     ap.add_argument("--probe-mfma", action="store_true",
                     help="time the MFMA-only loop of the debug build on random, constant and zero operands")
+    ap.add_argument("--probe-dq-atomics", action="store_true",
+                    help="time the fp32 atomic dQ reduction a single-pass backward would issue (debug build)")
     ap.add_argument("--paper-seq", type=int, default=0,
                     help="time the paper's Section 6.2 shape (B=4, H=32, D=128, non-causal) at this sequence length")
     ap.add_argument("--causal", action="store_true", help="with --paper-seq: the causal variant of that shape")
@@ -222,6 +258,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.probe_mfma:
         return probe_mfma(args, dev)
+    if args.probe_dq_atomics:
+        return probe_dq_atomics(args, dev)
     if args.splitkv:
         cfg = dict(name="long_B1_H8_Sq256_Skv%d_D128_full_split%d" % (args.long_skv, args.splitkv), B=1, H=8, S_q=256,
                    S_kv=args.long_skv, D=128, causal=False, seed=300, sharp=False, dtype="bf16")

@@ -1,10 +1,10 @@
 // attn_bwd_kernels.h -- attention backward for gfx950 (the pass of the paper's Section 6.3).
 //
-// The paper's single-pass algorithm is five GEMMs and one exponential per (query tile, key
-// tile) pair, followed by an atomic reduction of dQ into global memory; the paper itself
-// finds that reduction to be the bound once the tensor cores are fast enough.  Here the work
-// is split into two sweeps that need no atomics and no cross-workgroup reduction, so the
-// results are bitwise reproducible:
+// The paper's single-pass form (Section 6.3) runs five matrix products per (query tile, key tile)
+// pair and reduces dQ into global memory with atomics; the paper itself finds that reduction to
+// be the bound once the tensor cores are fast enough, and measured alone on this chip it takes
+// longer than the whole pass below.  Here the work is split into two sweeps that need no atomics
+// and no cross-workgroup reduction, so the results are bitwise reproducible:
 //
 //   KEY_OWNER = true   a workgroup owns 128 keys and streams query tiles:
 //                      S = Q K^T, dP = dO V^T, P = exp(S - LSE), dS = P o (dP - Delta),

@@ -319,6 +319,23 @@ extern "C" int attn_probe_mfma(const void *operands, float *out, int n_wg, int w
 }
 #endif
 
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+// Measurement entry point of the debug build: the atomic traffic of a single-pass backward's dQ reduction for
+// n_heads heads of S_q queries and S_kv keys (D = 128; S_q a multiple of 64, S_kv of 128) into dq (device,
+// n_heads * S_q * 128 floats, zeroed by the caller).
+extern "C" int attn_probe_dq_atomics(float *dq, int n_heads, int S_q, int S_kv, int causal, void *stream)
+{
+    if (!dq)
+        return ATTN_ERR_NULL;
+    if (n_heads < 1 || S_q < 64 || S_kv < 128 || S_q % 64 || S_kv % 128 || (long long)n_heads * (S_kv / 128) > 0x7fffffffLL)
+        return ATTN_ERR_SHAPE;
+    const int n_kt = S_kv / 128;
+    hipLaunchKernelGGL(attn::attn_probe_dq_atomics_kernel, dim3(n_heads * n_kt), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       dq, S_q, n_kt, causal);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+#endif
+
 extern "C" int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, long long head_bytes, int *head,
                                    int *tile)
 {

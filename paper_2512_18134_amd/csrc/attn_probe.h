@@ -1,6 +1,7 @@
 // attn_probe.h -- measurement kernels of the debug build (libmi355attn_debug.so), not part of the product
 // path: what the matrix pipe sustains when nothing else is issued, as the ceiling the attention kernels are
-// set against.
+// set against, and what the fp32 atomic reduction of dQ in the paper's single-pass backward (Section 6.3) costs
+// on its own.
 #pragma once
 #include "attn_common.h"
 
@@ -37,6 +38,29 @@ __global__ __launch_bounds__(NW * 64) void attn_probe_mfma_kernel(const bf16x8 *
         for (int r = 0; r < 16; ++r)
             s += acc[j][r];
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// The dQ reduction of the single-pass backward, alone.  A workgroup stands for one 128-key tile of one head
+// (D = 128) and adds, for every 64-query tile it would visit (causal: from the tile that holds its first key),
+// a 64 x 128 fp32 block of ones to dq[head][S_q][128] with hardware float atomics.  The access shape is the one
+// a kernel whose dQ accumulators have lane = head-dimension column would produce: wave w owns columns 32 w ..,
+// one instruction covers two query rows x 32 consecutive floats.  Afterwards dq[h][i][d] = number of key tiles
+// query i sees.
+__global__ __launch_bounds__(256) void attn_probe_dq_atomics_kernel(float *dq, int S_q, int n_kt, int causal)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int bh = blockIdx.x / n_kt, kt = blockIdx.x % n_kt;
+    const int n_qt = S_q / 64;
+    const int t_begin = causal ? min(kt * 2, n_qt) : 0;
+    float *head = dq + (size_t)bh * S_q * 128 + 32 * wave + (lane & 31);
+    for (int qt = t_begin; qt < n_qt; ++qt)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = qt * 64 + 32 * qb + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                unsafeAtomicAdd(head + (size_t)row * 128, 1.0f);
+            }
 }
 
 }  // namespace attn

@@ -215,3 +215,26 @@ def test_rejected_arguments(B):
     with pytest.raises(B.AttnError) as e:
         B.attn_bwd(z, z, z, z, z, lse)
     assert e.value.status == B.ATTN_ERR_UNSUPPORTED_D
+
+
+def test_dq_atomics_probe_counts_the_key_tiles_each_query_meets():
+    # the measurement kernel behind `bench.py --probe-dq-atomics` (debug build): after one launch every element
+    # of dq holds the number of 128-key tiles its query row meets -- exact in fp32 -- and bad shapes are refused
+    import ctypes
+    import debug_lib
+    lib = debug_lib.lib()
+    lib.attn_probe_dq_atomics.restype = ctypes.c_int
+    lib.attn_probe_dq_atomics.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+    st = torch.cuda.current_stream().cuda_stream
+    heads, s_q, s_kv = 3, 320, 384
+    for causal in (0, 1):
+        dq = torch.zeros((heads, s_q, 128), dtype=torch.float32, device="cuda:0")
+        assert lib.attn_probe_dq_atomics(dq.data_ptr(), heads, s_q, s_kv, causal, st) == 0
+        torch.cuda.synchronize()
+        rows = np.arange(s_q)
+        want = np.minimum(rows // 128 + 1, s_kv // 128) if causal else np.full(s_q, s_kv // 128)
+        assert np.array_equal(dq.cpu().numpy(), np.broadcast_to(want[None, :, None].astype(np.float32), (heads, s_q, 128)))
+    dq = torch.zeros((1, 64, 128), dtype=torch.float32, device="cuda:0")
+    for bad in ((1, 65, 128), (1, 64, 100), (0, 64, 128)):
+        assert lib.attn_probe_dq_atomics(dq.data_ptr(), bad[0], bad[1], bad[2], 0, st) != 0
+    assert lib.attn_probe_dq_atomics(None, 1, 64, 128, 0, st) != 0
