@@ -7,6 +7,7 @@
     python bench.py --paper-seq 16384 [--dtype f16]     # the paper's own sweep shape (Section 6.2)
     python bench.py --probe-mfma                        # matrix-pipe ceiling: MFMA-only loop of the debug build
     python bench.py --probe-dq-atomics                  # cost of a single-pass backward's atomic dQ reduction alone
+    python bench.py --timeline --config 3               # per-workgroup phase timing of one forward launch (debug build)
 
 A "step" is one attn_fwd call (the whole hot path) over one batch of seeded
 synthetic Q/K/V that is already resident in HBM.  Prints ONE JSON line.
@@ -206,6 +207,69 @@ def probe_dq_atomics(args, dev):
     print(json.dumps({"probe": "fp32 atomic dQ reduction of a single-pass backward, B4 H32 D128", "results": res}), flush=True)
 
 
+def timeline(args, dev):
+    """Where the time of one forward launch goes: attn_fwd_trace of the debug build records, per workgroup,
+    a constant-rate clock (10 ns) at kernel entry, after K(0) and Q have landed, before and after the main
+    loop, after O is staged, and at the end, plus the CU it ran on.  Prints one JSON line: the launch's span,
+    the mean and maximum of every phase, and per CU the start of its first workgroup (dispatch ramp), the gaps
+    between its workgroups and the end of its last one (tail)."""
+    import ctypes
+    import torch
+    from paper_2512_18134_amd import synth
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2512_18134_amd", "libmi355attn_debug.so"))
+    lib.attn_fwd_trace.restype = ctypes.c_int
+    lib.attn_fwd_trace.argtypes = ([ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p,
+                                                                                ctypes.c_void_p, ctypes.c_longlong])
+    cfg, q, k, v, scale = synth.make_config(args.config)
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    B, H, S_q, S_kv, D = cfg["B"], cfg["H"], cfg["S_q"], cfg["S_kv"], cfg["D"]
+    o = torch.empty_like(qd)
+    lse = torch.empty((B, H, S_q), dtype=torch.float32, device=dev)
+    n_rec = B * H * ((S_q + 127) // 128)                    # at least one record per workgroup of any tiling
+    trace = torch.zeros((n_rec, 8), dtype=torch.int64, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    call = lambda: lib.attn_fwd_trace(qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H,
+                                      S_q, S_kv, D, int(cfg["causal"]), scale, stream.cuda_stream, trace.data_ptr(),
+                                      trace.numel())
+    for _ in range(max(args.warmup, 3)):
+        assert call() == 0
+    torch.cuda.synchronize()
+    trace.zero_()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    assert call() == 0
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t = trace.cpu().numpy()
+    t = t[t[:, 0] != 0]
+    us = (t[:, :6] - t[:, 0].min()) / 100.0                 # microseconds since the first workgroup started
+    hw, xcc = t[:, 6], t[:, 7] & 0xF
+    cu_key = (xcc << 16) | (((hw >> 13) & 7) << 8) | (((hw >> 12) & 1) << 4) | ((hw >> 8) & 0xF)
+    phases = {"wait_k0_q": us[:, 1] - us[:, 0], "s0_and_setup": us[:, 2] - us[:, 1], "loop": us[:, 3] - us[:, 2],
+              "normalise_and_stage_o": us[:, 4] - us[:, 3], "store_o": us[:, 5] - us[:, 4]}
+    first, last, gaps, per_cu = [], [], [], []
+    for key in np.unique(cu_key):
+        w = us[cu_key == key]
+        w = w[np.argsort(w[:, 0])]
+        first.append(w[0, 0])
+        last.append(w[:, 5].max())
+        per_cu.append(len(w))
+        # workgroups of one CU that do not overlap: idle time between the end of one and the start of the next
+        ends = np.maximum.accumulate(w[:, 5])
+        gaps += [max(0.0, float(w[i + 1, 0] - ends[i])) for i in range(len(w) - 1)]
+    span = float(us[:, 5].max())
+    out = {"timeline": cfg["name"], "workgroups": int(len(t)), "cus_used": int(len(first)),
+           "event_ms": e0.elapsed_time(e1), "span_us": span,
+           "phase_us_mean_max": {k: [float(x.mean()), float(x.max())] for k, x in phases.items()},
+           "workgroups_per_cu_min_mean_max": [int(min(per_cu)), float(np.mean(per_cu)), int(max(per_cu))],
+           "first_start_per_cu_us_mean_max": [float(np.mean(first)), float(np.max(first))],
+           "gap_between_workgroups_us_mean_max": [float(np.mean(gaps)) if gaps else 0.0, float(np.max(gaps)) if gaps else 0.0],
+           "idle_before_span_end_per_cu_us_mean_max": [float(np.mean(span - np.array(last))), float(np.max(span - np.array(last)))],
+           "loop_share_of_cu_time": float(phases["loop"].sum() / (len(first) * span))}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -220,6 +284,8 @@ def main():
                     help="time the MFMA-only loop of the debug build on random, constant and zero operands")
     ap.add_argument("--probe-dq-atomics", action="store_true",
                     help="time the fp32 atomic dQ reduction a single-pass backward would issue (debug build)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-workgroup phase timing of one forward launch of --config (debug build)")
     ap.add_argument("--paper-seq", type=int, default=0,
                     help="time the paper's Section 6.2 shape (B=4, H=32, D=128, non-causal) at this sequence length")
     ap.add_argument("--causal", action="store_true", help="with --paper-seq: the causal variant of that shape")
@@ -260,6 +326,8 @@ def main():
         return probe_mfma(args, dev)
     if args.probe_dq_atomics:
         return probe_dq_atomics(args, dev)
+    if args.timeline:
+        return timeline(args, dev)
     if args.splitkv:
         cfg = dict(name="long_B1_H8_Sq256_Skv%d_D128_full_split%d" % (args.long_skv, args.splitkv), B=1, H=8, S_q=256,
                    S_kv=args.long_skv, D=128, causal=False, seed=300, sharp=False, dtype="bf16")

@@ -84,7 +84,28 @@ struct Params {
     int n_split, split_len;
     float *o_part;    // [n_split][B*H*S_q][D] fp32
     float *lse_part;  // [n_split][B*H*S_q] fp32
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+    // debug build only (attn_fwd_trace): per workgroup 8 values -- the 100 MHz clock at six points of the kernel,
+    // then the hardware id and XCC id registers of the workgroup's first wave; NULL = no trace
+    unsigned long long *trace;
+    long long trace_entries;
+#endif
 };
+
+// ATTN_TRACE(p, slot): in the debug build, every lane of a workgroup stores the constant-rate clock (or
+// `value`) into the workgroup's trace record (uniform control flow; the last writer's value stays); nothing in
+// the product build.
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+#define ATTN_TRACE_VALUE(p, slot, value)                                                                       \
+    do {                                                                                                       \
+        if ((p).trace && ((long long)blockIdx.x + 1) * 8 <= (p).trace_entries)             \
+            (p).trace[(size_t)blockIdx.x * 8 + (slot)] = (unsigned long long)(value);                         \
+    } while (0)
+#define ATTN_TRACE(p, slot) ATTN_TRACE_VALUE(p, slot, __builtin_amdgcn_s_memrealtime())
+#else
+#define ATTN_TRACE_VALUE(p, slot, value) ((void)0)
+#define ATTN_TRACE(p, slot) ((void)0)
+#endif
 
 // Workgroup id -> (batch*head, query tile).
 //  * not causal: all tiles cost the same; every XCD takes a contiguous range of (bh, qt) pairs.

@@ -138,6 +138,10 @@ static int validate(const void *q, const void *k, const void *v, void *o, float 
     p.c = scale * 1.44269504088896340736f;
     p.scale = scale;
     p.n_split = 1;
+#ifdef ATTN_DEBUG_ENTRY_POINTS
+    p.trace = nullptr;
+    p.trace_entries = 0;
+#endif
     p.split_len = 0;
     p.o_part = nullptr;
     p.lse_part = nullptr;
@@ -300,6 +304,26 @@ extern "C" int attn_fwd_variant(const void *q, const void *k, const void *v, voi
 #endif
 
 #ifdef ATTN_DEBUG_ENTRY_POINTS
+// Measurement entry point of the debug build: attn_fwd (hand-scheduled kernels) that also records, per
+// workgroup w, trace[8 w + 0..5] = the 100 MHz constant clock at kernel entry, after K(0) and Q have landed,
+// before the main loop, after it, after O is staged in LDS, and at the end; trace[8 w + 6] = the HW_ID
+// register (CU, SE, ...) and trace[8 w + 7] = XCC_ID of the workgroup's first wave.  trace: device,
+// trace_entries 64-bit values; workgroups whose record would not fit write nothing.
+extern "C" int attn_fwd_trace(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
+                              int S_kv, int D, int causal, float scale, void *stream, unsigned long long *trace,
+                              long long trace_entries)
+{
+    Params p;
+    const int rc = validate(q, k, v, o, lse, B, H, S_q, S_kv, D, scale, p);
+    if (rc != ATTN_OK)
+        return rc;
+    if (!trace || trace_entries < 8)
+        return ATTN_ERR_NULL;
+    p.trace = trace;
+    p.trace_entries = trace_entries;
+    return dispatch_fwd(p, B * H, D, causal, static_cast<hipStream_t>(stream));
+}
+
 // Measurement entry point of the debug build: n_wg workgroups of waves_per_wg (4 or 8) waves, each wave
 // `iters` x 8 MFMAs (32768 FLOP each) on the 8 fragments at `operands` (device, 8 * 64 * 16 bytes: 4 A then 4 B
 // fragments, 16 bytes per lane); `out` (device, n_wg * waves_per_wg * 64 floats) receives one value per lane.

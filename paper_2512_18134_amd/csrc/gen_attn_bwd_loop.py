@@ -40,10 +40,24 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 from asm_emit import Emitter  # noqa: E402
 
 
+# (key owner?, D) -> NF: fragment buffers; PFD: MFMA slots between a fragment's LDS read and its use;
+# W: fragment groups per s_waitcnt
+DEFAULTS = {
+    (True, 128):  dict(NF=8, PFD=6, W=2),
+    (False, 128): dict(NF=8, PFD=4, W=2),
+    (True, 64):   dict(NF=8, PFD=4, W=2),
+    (False, 64):  dict(NF=4, PFD=2, W=1),
+}
+
+
 class Gen(Emitter):
-    def __init__(self, key_owner, D, NF=4, PFD=3, dtype="bf16", drop=()):
+    def __init__(self, key_owner, D, NF=None, PFD=None, dtype="bf16", drop=(), W=None):
         Emitter.__init__(self)
         assert D in (64, 128) and dtype in ("bf16", "f16")
+        dflt = DEFAULTS[(bool(key_owner), D)]
+        NF = dflt["NF"] if NF is None else NF
+        PFD = dflt["PFD"] if PFD is None else PFD
+        W = dflt["W"] if W is None else W
         self.KO = key_owner
         # the two element types differ only in the MFMA and in the pack instruction (both round to nearest even)
         self.dtype = dtype
@@ -62,7 +76,7 @@ class Gen(Emitter):
         self.NSET = 2 if key_owner else 1            # accumulator sets: (dK, dV) or (dQ)
         self.NC = self.NSET * self.DB                # contraction MFMAs per 16-row chunk
         PFD = min(PFD, self.NC)                      # the prefetched operands belong to the first chunk (see drain)
-        self.NF, self.PFD = NF, PFD
+        self.NF, self.PFD, self.W = NF, PFD, W           # W: fragment groups per s_waitcnt
         self.NM = 2 * self.NC + 2 * self.KS          # MFMA slots per iteration
         self.NGRP = 2 * self.NLD + (1 if key_owner else 0)  # direct loads per wave and tile
         assert self.NM % NF == 0 and PFD < NF
@@ -266,7 +280,8 @@ class Gen(Emitter):
         if "nolds" in self.exp:
             lds_by_slot = {}
         self.stream(grps, lambda g, buf: [self.mfma_text(g, buf, bf)], lambda g, buf: loads(g, buf, rst, tst),
-                    self.NF, self.PFD, valu_by_slot, extra_by_slot, nxt_loads, lds_by_slot=lds_by_slot)
+                    self.NF, self.PFD, valu_by_slot, extra_by_slot, nxt_loads, lds_by_slot=lds_by_slot,
+                    wait_every=self.W)
 
     # --------------------------------------------------------------- the loop
     def body(self, b):
@@ -319,7 +334,7 @@ class Gen(Emitter):
         if "novalu" in self.exp:
             valu = {}
         if "nodma" in self.exp:
-            extra = {2: extra[2]}
+            extra = {0: ["%s:" % L("SLOWRET%d_" % b)], 2: extra[2]}
         self.run_stream(self.groups(), bf, rst, tst, valu, extra, lds, nxt)
         if b == NST - 1:
             self.e("s_branch %s" % L("BODY0_"))
@@ -453,19 +468,21 @@ class Gen(Emitter):
 
 
 if __name__ == "__main__":
-    # --nf / --pfd / --drop: timing experiments (fragment buffers, prefetch distance, parts left out);
+    # --nf / --pfd / --w / --drop: timing experiments (fragment buffers, prefetch distance, groups per wait, parts left out);
     # a library build passes none of them
     args = sys.argv[1:]
-    nf, pfd, drop = 4, 3, ()
-    while len(args) > 3 and args[-2] in ("--nf", "--pfd", "--drop"):
+    nf, pfd, w, drop = None, None, None, ()
+    while len(args) > 3 and args[-2] in ("--nf", "--pfd", "--w", "--drop"):
         if args[-2] == "--nf":
             nf = int(args[-1])
         elif args[-2] == "--pfd":
             pfd = int(args[-1])
+        elif args[-2] == "--w":
+            w = int(args[-1])
         else:
             drop = tuple(filter(None, args[-1].split(",")))
         args = args[:-2]
     dtype = args[3] if len(args) > 3 else "bf16"
-    text = Gen(args[0] == "kv", int(args[1]), NF=nf, PFD=pfd, dtype=dtype, drop=drop).emit_inc()
+    text = Gen(args[0] == "kv", int(args[1]), NF=nf, PFD=pfd, dtype=dtype, drop=drop, W=w).emit_inc()
     with open(args[2], "w") as f:
         f.write(text)
