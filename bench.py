@@ -209,8 +209,10 @@ def probe_dq_atomics(args, dev):
 
 def timeline(args, dev):
     """Where the time of one forward launch goes: attn_fwd_trace of the debug build records, per workgroup,
-    a constant-rate clock (10 ns) at kernel entry, after K(0) and Q have landed, before and after the main
-    loop, after O is staged, and at the end, plus the CU it ran on.  Prints one JSON line: the launch's span,
+    a constant-rate clock (10 ns) when a tile is taken up, when its first loads are issued, after K(0) and Q
+    have landed, before and after the main loop, after O is staged, and when O is stored, plus the CU it ran on
+    (behind a finished tile the persistent kernels issue the next tile's loads before they write the finished
+    one out, so the two tiles' records overlap there).  Prints one JSON line: the launch's span,
     the mean and maximum of every phase, and per CU the start of its first workgroup (dispatch ramp), the gaps
     between its workgroups and the end of its last one (tail)."""
     import ctypes
@@ -244,10 +246,17 @@ def timeline(args, dev):
     t = trace.cpu().numpy()
     t = t[t[:, 0] != 0]
     us = (t[:, :6] - t[:, 0].min()) / 100.0                 # microseconds since the first workgroup started
-    hw, xcc = t[:, 6], t[:, 7] & 0xF
+    hw, xcc = t[:, 7] & 0xFFFFFFFF, (t[:, 7] >> 32) & 0xF
+    issued = (t[:, 6] - t[:, 0].min()) / 100.0
     cu_key = (xcc << 16) | (((hw >> 13) & 7) << 8) | (((hw >> 12) & 1) << 4) | ((hw >> 8) & 0xF)
-    phases = {"wait_k0_q": us[:, 1] - us[:, 0], "s0_and_setup": us[:, 2] - us[:, 1], "loop": us[:, 3] - us[:, 2],
-              "normalise_and_stage_o": us[:, 4] - us[:, 3], "store_o": us[:, 5] - us[:, 4]}
+    phases = {"take_up_to_loads_issued": issued - us[:, 0], "loads_issued_to_k0_q_landed": us[:, 1] - issued,
+              "s0_and_setup": us[:, 2] - us[:, 1], "loop": us[:, 3] - us[:, 2],
+              "loop_end_to_o_staged": us[:, 4] - us[:, 3], "store_o": us[:, 5] - us[:, 4]}
+    # a CU's first tile starts cold; later tiles of a persistent workgroup are taken up behind the previous loop
+    is_first = np.zeros(len(t), dtype=bool)
+    for key in np.unique(cu_key):
+        idx = np.nonzero(cu_key == key)[0]
+        is_first[idx[np.argmin(us[idx, 0])]] = True
     first, last, gaps, per_cu = [], [], [], []
     for key in np.unique(cu_key):
         w = us[cu_key == key]
@@ -262,6 +271,8 @@ def timeline(args, dev):
     out = {"timeline": cfg["name"], "workgroups": int(len(t)), "cus_used": int(len(first)),
            "event_ms": e0.elapsed_time(e1), "span_us": span,
            "phase_us_mean_max": {k: [float(x.mean()), float(x.max())] for k, x in phases.items()},
+           "phase_us_mean_first_tile_of_cu": {k: float(x[is_first].mean()) for k, x in phases.items()},
+           "phase_us_mean_later_tiles": {k: (float(x[~is_first].mean()) if (~is_first).any() else None) for k, x in phases.items()},
            "workgroups_per_cu_min_mean_max": [int(min(per_cu)), float(np.mean(per_cu)), int(max(per_cu))],
            "first_start_per_cu_us_mean_max": [float(np.mean(first)), float(np.max(first))],
            "gap_between_workgroups_us_mean_max": [float(np.mean(gaps)) if gaps else 0.0, float(np.max(gaps)) if gaps else 0.0],

@@ -136,6 +136,18 @@ long long attn_fwd_splitkv_workspace_bytes(int B, int H, int S_q, int D, int n_s
 int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n_tiles, long long head_bytes,
                         int *head, int *tile);
 
+/*
+ * Diagnostic, host only (no GPU call): the forward kernels' workgroups are persistent -- a launch has at most
+ * one workgroup per CU slot and each walks a queue of tiles.  `*entry` = the id (the `workgroup` argument of
+ * attn_workgroup_tile) that workgroup `workgroup` of a launch of n_workgroups takes up in pass `pass` (0, 1, ...)
+ * when n_entries tiles are queued, or -1 when that pass has none for it.  An XCD's workgroups share the XCD's
+ * entries (id % 8); odd passes run through them in reverse, so that a slot pairs heavy with light tiles of a
+ * causal launch.  n_workgroups >= n_entries: one entry each, in pass 0.
+ * Returns ATTN_OK, or ATTN_ERR_NULL / ATTN_ERR_SHAPE (counts < 1, pass < 0, workgroup outside
+ * [0, n_workgroups), n_workgroups < n_entries and not a multiple of 8).
+ */
+int attn_workgroup_queue_entry(int workgroup, int n_workgroups, int n_entries, int pass, int *entry);
+
 /* Static, NUL-terminated description of an attn_status value; never freed. */
 const char *attn_strerror(int status);
 

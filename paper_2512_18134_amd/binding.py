@@ -66,6 +66,21 @@ def attn_version():
     return int(_lib.attn_version())
 
 
+_lib.attn_workgroup_queue_entry.restype = ctypes.c_int
+_lib.attn_workgroup_queue_entry.argtypes = [ctypes.c_int] * 4 + [ctypes.POINTER(ctypes.c_int)]
+
+
+def attn_workgroup_queue_entry(workgroup, n_workgroups, n_entries, pass_):
+    """Host-side view of the persistent forward launch: the queue entry workgroup `workgroup` takes up in pass
+    `pass_`, or -1."""
+    entry = ctypes.c_int(-2)
+    rc = int(_lib.attn_workgroup_queue_entry(int(workgroup), int(n_workgroups), int(n_entries), int(pass_),
+                                             ctypes.byref(entry)))
+    if rc != ATTN_OK:
+        raise AttnError(rc)
+    return entry.value
+
+
 def attn_workgroup_tile(causal, workgroup, n_heads, n_tiles, head_bytes=0):
     """attn_workgroup_tile (host-only diagnostic): the (head, tile) that workgroup id works on."""
     head, tile = ctypes.c_int(-1), ctypes.c_int(-1)

@@ -52,6 +52,22 @@ __host__ __device__ __forceinline__ int xcd_remap(int wid, int total)
     return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + slot;
 }
 
+// Persistent launches: n_slots workgroups (a multiple of the XCD count) share a queue of n_entries tiles, which
+// workgroup ids map to as above (entry e belongs to XCD e % 8).  Workgroup `wg` walks the queue of its XCD:
+// pass k takes the XCD's entry k*S + m (S = n_slots / 8 slots per XCD, m = wg / 8), odd passes in reverse
+// (k*S + S-1-m): with entries queued heaviest first a slot then pairs heavy with light, like a dispatcher
+// that hands the next entry to the workgroup that finishes first.  Returns the entry, or -1 when pass k has
+// none for this workgroup (only the last pass can be short).  n_slots == n_entries: one entry each.
+__host__ __device__ __forceinline__ int persistent_entry(int wg, int n_slots, int n_entries, int k)
+{
+    if (n_slots >= n_entries)
+        return k == 0 && wg < n_entries ? wg : -1;
+    const int xcd = wg % kNumXcd, m = wg / kNumXcd, S = n_slots / kNumXcd;
+    const int n_x = (n_entries - xcd + kNumXcd - 1) / kNumXcd;  // queue length of this XCD
+    const int idx = k * S + ((k & 1) ? S - 1 - m : m);
+    return idx < n_x ? idx * kNumXcd + xcd : -1;
+}
+
 // Causal launches hand out an XCD's workgroups in heaviest-first groups of whole heads: between 32
 // workgroups (one per CU of the XCD) and 128, as many heads as stream no more than one L2 (4 MB) of
 // operands between them; heads whose operands do not fit an L2 twice over share it by streaming in step
@@ -92,19 +108,19 @@ struct Params {
 #endif
 };
 
-// ATTN_TRACE(p, slot): in the debug build, every lane of a workgroup stores the constant-rate clock (or
-// `value`) into the workgroup's trace record (uniform control flow; the last writer's value stays); nothing in
+// ATTN_TRACE(p, wg, slot): in the debug build, every lane of a workgroup stores the constant-rate clock (or
+// `value`) into the trace record of tile `wg` (its index in the tile queue) (uniform control flow; the last writer's value stays); nothing in
 // the product build.
 #ifdef ATTN_DEBUG_ENTRY_POINTS
-#define ATTN_TRACE_VALUE(p, slot, value)                                                                       \
-    do {                                                                                                       \
-        if ((p).trace && ((long long)blockIdx.x + 1) * 8 <= (p).trace_entries)             \
-            (p).trace[(size_t)blockIdx.x * 8 + (slot)] = (unsigned long long)(value);                         \
+#define ATTN_TRACE_VALUE(p, wg, slot, value)                                                   \
+    do {                                                                                       \
+        if ((p).trace && ((long long)(wg) + 1) * 8 <= (p).trace_entries)                       \
+            (p).trace[(size_t)(wg) * 8 + (slot)] = (unsigned long long)(value);                \
     } while (0)
-#define ATTN_TRACE(p, slot) ATTN_TRACE_VALUE(p, slot, __builtin_amdgcn_s_memrealtime())
+#define ATTN_TRACE(p, wg, slot) ATTN_TRACE_VALUE(p, wg, slot, __builtin_amdgcn_s_memrealtime())
 #else
-#define ATTN_TRACE_VALUE(p, slot, value) ((void)0)
-#define ATTN_TRACE(p, slot) ((void)0)
+#define ATTN_TRACE_VALUE(p, wg, slot, value) ((void)0)
+#define ATTN_TRACE(p, wg, slot) ((void)0)
 #endif
 
 // Workgroup id -> (batch*head, query tile).

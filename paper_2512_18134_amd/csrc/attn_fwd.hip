@@ -22,8 +22,10 @@ constexpr int kW4MaxKeys = 4096;  // D = 64, causal: up to this many keys the 4-
 
 using attn::allow_lds;
 
+// wgs_per_cu: 0 = one workgroup per tile; > 0 = persistent workgroups, that many per CU, each walking the tile
+// queue of its XCD (attn_fwd_asm_kernel)
 template <typename K>
-int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStream_t stream)
+int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStream_t stream, int wgs_per_cu = 0)
 {
     p.n_qt = (p.S_q + BM - 1) / BM;
     const long long total = (long long)BH * p.n_qt;
@@ -32,7 +34,15 @@ int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStre
     p.total_wg = (int)total;
     if (!allow_lds(reinterpret_cast<const void *>(kern), lds_bytes))
         return ATTN_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(threads), lds_bytes, stream, p);
+    int grid = p.total_wg;
+    if (wgs_per_cu > 0) {
+        const int slots = attn::cu_count(attn::kNumXcd) * wgs_per_cu;
+        if (slots < attn::kNumXcd)
+            return ATTN_ERR_LAUNCH;
+        if (slots < grid)
+            grid = slots;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
@@ -45,14 +55,17 @@ int launch_simple(const Params &p, int BH, int causal, hipStream_t stream)
     return launch(attn::attn_fwd_simple_kernel<D, BN, NW, false>, p, BH, NW * 32, NW * 64, LDS, stream);
 }
 
-// one hand-scheduled tiling: QB 32-row query blocks per wave, SB 32-key blocks per K/V tile, NW waves
+// one hand-scheduled tiling: QB 32-row query blocks per wave, SB 32-key blocks per K/V tile, NW waves; persistent
+// workgroups where the tiling has them, one per CU (two of the 4-wave D = 64 workgroups)
 template <int D, int QB, int SB, int NW, bool F16 = false>
 int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
 {
-    constexpr int LDS = 8 * 32 * SB * D * 2, BM = 32 * QB * NW;
+    typedef attn::FwdTiling<D, QB, SB, NW, false> T;
     if (causal)
-        return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, true, F16>, p, BH, BM, NW * 64, LDS, stream);
-    return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, false, F16>, p, BH, BM, NW * 64, LDS, stream);
+        return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, true, F16>, p, BH, T::BM, NW * 64, T::LDS_BYTES, stream,
+                      T::WGS_PER_CU);
+    return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, false, F16>, p, BH, T::BM, NW * 64, T::LDS_BYTES, stream,
+                  T::WGS_PER_CU);
 }
 
 // D = 64.  w4: -1 = choose, 0 / 1 = 8-wave / 4-wave workgroups.
@@ -174,8 +187,8 @@ static int launch_splitkv(Params &p, int BH, int n_eff, void *o, float *lse, hip
     if (total > 0x7fffffffLL)
         return ATTN_ERR_SHAPE;
     p.total_wg = (int)total;
-    const int lds = 8 * 64 * D * 2;
-    auto kern = attn::attn_fwd_asm_kernel<D, 1, 2, 8, false, F16, true>;
+    const int lds = attn::FwdTiling<D, 1, 2, 8, true>::LDS_BYTES;
+    auto kern = attn::attn_fwd_asm_kernel<D, 1, 2, 8, false, F16, true>;   // one workgroup per (tile, key range)
     if (!allow_lds(reinterpret_cast<const void *>(kern), lds))
         return ATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(512), lds, st, p);
@@ -305,9 +318,10 @@ extern "C" int attn_fwd_variant(const void *q, const void *k, const void *v, voi
 
 #ifdef ATTN_DEBUG_ENTRY_POINTS
 // Measurement entry point of the debug build: attn_fwd (hand-scheduled kernels) that also records, per
-// workgroup w, trace[8 w + 0..5] = the 100 MHz constant clock at kernel entry, after K(0) and Q have landed,
-// before the main loop, after it, after O is staged in LDS, and at the end; trace[8 w + 6] = the HW_ID
-// register (CU, SE, ...) and trace[8 w + 7] = XCC_ID of the workgroup's first wave.  trace: device,
+// tile w of the launch's queue, trace[8 w + 0..5] = the 100 MHz constant clock when the tile is taken up, after
+// K(0) and Q have landed, before the main loop, after it, after O is staged in LDS, and when O is stored;
+// trace[8 w + 6] = the clock when the tile's first loads are all issued; trace[8 w + 7] = XCC_ID << 32 | HW_ID
+// (CU, SE, ...) of a wave of the workgroup.  trace: device,
 // trace_entries 64-bit values; workgroups whose record would not fit write nothing.
 extern "C" int attn_fwd_trace(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
                               int S_kv, int D, int causal, float scale, void *stream, unsigned long long *trace,
@@ -372,6 +386,17 @@ extern "C" int attn_workgroup_tile(int causal, int workgroup, int n_heads, int n
         attn::wg_to_tile_n<true>(workgroup, n_heads * n_tiles, n_tiles, head_bytes, *head, *tile);
     else
         attn::wg_to_tile_n<false>(workgroup, n_heads * n_tiles, n_tiles, head_bytes, *head, *tile);
+    return ATTN_OK;
+}
+
+extern "C" int attn_workgroup_queue_entry(int workgroup, int n_workgroups, int n_entries, int pass, int *entry)
+{
+    if (!entry)
+        return ATTN_ERR_NULL;
+    if (n_workgroups < 1 || n_entries < 1 || pass < 0 || workgroup < 0 || workgroup >= n_workgroups ||
+        (n_workgroups < n_entries && n_workgroups % attn::kNumXcd))
+        return ATTN_ERR_SHAPE;
+    *entry = attn::persistent_entry(workgroup, n_workgroups, n_entries, pass);
     return ATTN_OK;
 }
 

@@ -1,4 +1,4 @@
-// attn_launch.h -- host-side launch helper shared by the entry points.
+// attn_launch.h -- host-side launch helpers shared by the entry points.
 #pragma once
 #include <stdint.h>
 
@@ -32,6 +32,28 @@ inline bool allow_lds(const void *kern, int bytes)
     }
     mask |= 1ull << dev;
     return true;
+}
+
+// Compute units of the current device (asked once per device), rounded down to a multiple of `multiple`;
+// 0 when the runtime cannot tell.
+inline int cu_count(int multiple)
+{
+    constexpr int kMaxDev = 64;
+    static std::mutex mu;
+    static int cached[kMaxDev] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev)
+        return 0;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            return 0;
+        }
+        cached[dev] = n;
+    }
+    return cached[dev] / multiple * multiple;
 }
 
 }  // namespace attn

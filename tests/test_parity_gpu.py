@@ -312,3 +312,25 @@ def test_tiling_variants_agree_with_the_oracle(B):
         orf, lrf = attn_ref(q, k, v, causal, scale)
         assert np.max(np.abs(o_to_f64(o) - orf)) <= O_TOL, (D, causal, variant)
         assert np.max(np.abs(lse.cpu().numpy().astype(np.float64) - lrf)) <= LSE_TOL, (D, causal, variant)
+
+
+MANY_TILES = [
+    # more query tiles than the chip has CU slots, so that the persistent workgroups walk their queues through
+    # several passes, the last one short; few keys keep the oracle cheap.  B, H, S_q, S_kv, D, causal
+    (1, 3, 25600 + 17, 64, 128, False),    # 303 tiles of 256 rows: one full pass, a short second one
+    (1, 5, 33000, 96, 128, True),          # 645 tiles: two full passes and a short third
+    (2, 2, 40000, 70, 64, False),          # 628 tiles of 256 rows
+    (1, 1, 76800 + 5, 40, 256, True),      # 601 tiles of 128 rows
+    (1, 9, 7500, 150, 64, True),           # 4-wave D = 64 workgroups (two per CU): 531 tiles of 128 rows
+]
+
+
+@pytest.mark.parametrize("shape", MANY_TILES, ids=lambda s: "B%d_H%d_Sq%d_Skv%d_D%d_%s" % (s[0], s[1], s[2], s[3], s[4], "causal" if s[5] else "full"))
+def test_more_tiles_than_cu_slots(B, shape):
+    b, h, sq, skv, d, causal = shape
+    print("case", shape, flush=True)
+    q, k, v = synth.make_qkv(b, h, sq, skv, d, seed=7 + d)
+    og, lg = check_full(B, q, k, v, causal, synth.default_scale(d), str(shape))
+    # a second launch on the same buffers gives the same bits (the walk is static)
+    og2, lg2 = run_gpu(B, q, k, v, causal, synth.default_scale(d))
+    assert np.array_equal(og, og2) and np.array_equal(lg, lg2)

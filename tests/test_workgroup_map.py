@@ -118,3 +118,62 @@ def test_group_sizes_follow_the_l2(B):
         queue = table(B, True, 128, 4, head_bytes)[0::N_XCD]
         first_group = {h for h, _ in queue[:heads * 4]}
         assert len(first_group) == heads and len({h for h, _ in queue[:heads * 4 + 1]}) == heads + (heads < 16)
+
+
+def queue_walk(B, n_wg, n_entries):
+    """{workgroup: [entries in pass order]} of a persistent launch, walked until a pass is empty for everybody."""
+    walk = {w: [] for w in range(n_wg)}
+    k = 0
+    while True:
+        got = [B.attn_workgroup_queue_entry(w, n_wg, n_entries, k) for w in range(n_wg)]
+        if all(e < 0 for e in got):
+            return walk
+        for w, e in enumerate(got):
+            if e >= 0:
+                walk[w].append(e)
+        k += 1
+        assert k < 10000
+
+
+def test_persistent_workgroups_take_every_queue_entry_once(B):
+    for n_wg, n_entries in ((256, 512), (256, 1024), (256, 257), (256, 300), (512, 513), (512, 2048), (8, 9), (8, 1000),
+                            (16, 23), (256, 256), (300, 200), (7, 7), (256, 1), (264, 1000)):
+        walk = queue_walk(B, n_wg, n_entries)
+        seen = sorted(e for es in walk.values() for e in es)
+        assert seen == list(range(n_entries)), (n_wg, n_entries)
+        if n_wg < n_entries:
+            for w, es in walk.items():
+                # a workgroup stays on its XCD's entries, never skips a pass before its last, and the numbers of
+                # entries of two workgroups differ by one at most
+                assert all(e % 8 == w % 8 for e in es)
+                assert len(es) >= 1
+            sizes = [len(es) for es in walk.values()]
+            assert max(sizes) - min(sizes) <= 1
+
+
+def test_persistent_walk_pairs_heavy_with_light(B):
+    # entries queued heaviest first (a causal launch): weight of entry e falls with e.  Two passes over 256
+    # slots: every slot's load is the same up to one step of the weight
+    n_wg, n_entries = 256, 512
+    walk = queue_walk(B, n_wg, n_entries)
+    weight = lambda e: n_entries // 8 - e // 8          # an XCD's queue position decides the weight
+    loads = [sum(weight(e) for e in es) for es in walk.values()]
+    assert max(loads) - min(loads) == 0
+    # four passes: still even
+    walk = queue_walk(B, 256, 1024)
+    weight = lambda e: 1024 // 8 - e // 8
+    loads = [sum(weight(e) for e in es) for es in walk.values()]
+    assert max(loads) - min(loads) == 0
+    # a third, short pass goes to the slots that got the lighter pairs... at least nobody gets two more than another
+    walk = queue_walk(B, 256, 600)
+    assert max(len(es) for es in walk.values()) - min(len(es) for es in walk.values()) <= 1
+
+
+def test_queue_entry_arguments_are_checked(B):
+    for bad in [(0, 0, 4, 0), (0, 4, 0, 0), (-1, 8, 16, 0), (8, 8, 16, 0), (0, 8, 16, -1), (0, 12, 16, 0)]:
+        with pytest.raises(B.AttnError) as e:
+            B.attn_workgroup_queue_entry(*bad)
+        assert e.value.status == B.ATTN_ERR_SHAPE
+    lib = ctypes.CDLL(B._lib._name)
+    lib.attn_workgroup_queue_entry.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p]
+    assert lib.attn_workgroup_queue_entry(0, 8, 16, 0, None) == B.ATTN_ERR_NULL
