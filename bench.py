@@ -268,6 +268,11 @@ def timeline(args, dev):
         ends = np.maximum.accumulate(w[:, 5])
         gaps += [max(0.0, float(w[i + 1, 0] - ends[i])) for i in range(len(w) - 1)]
     span = float(us[:, 5].max())
+    xcd_of = {int(key): int(key) >> 16 for key in np.unique(cu_key)}
+    keys = [int(key) for key in np.unique(cu_key)]
+    end_by_xcd = {}
+    for key, e in zip(keys, last):
+        end_by_xcd.setdefault(xcd_of[key], []).append(e)
     out = {"timeline": cfg["name"], "workgroups": int(len(t)), "cus_used": int(len(first)),
            "event_ms": e0.elapsed_time(e1), "span_us": span,
            "phase_us_mean_max": {k: [float(x.mean()), float(x.max())] for k, x in phases.items()},
@@ -277,6 +282,8 @@ def timeline(args, dev):
            "first_start_per_cu_us_mean_max": [float(np.mean(first)), float(np.max(first))],
            "gap_between_workgroups_us_mean_max": [float(np.mean(gaps)) if gaps else 0.0, float(np.max(gaps)) if gaps else 0.0],
            "idle_before_span_end_per_cu_us_mean_max": [float(np.mean(span - np.array(last))), float(np.max(span - np.array(last)))],
+           "last_end_per_xcd_us_mean_min_max": {str(x): [float(np.mean(v)), float(np.min(v)), float(np.max(v))]
+                                                for x, v in sorted(end_by_xcd.items())},
            "loop_share_of_cu_time": float(phases["loop"].sum() / (len(first) * span))}
     print(json.dumps(out), flush=True)
 

@@ -42,7 +42,8 @@ On N(0,1) inputs this pass runs once per workgroup.
 
 Rare events share one test per iteration: j >= s_special (last tile, tiles that
 need a mask, tiles whose loads reach past S_kv) branches out of line and comes
-back with SCC set, which the two load slots test again.
+back with SCC saying whether this iteration's loads need their rows clamped,
+which the two load slots test.
 
 The ramp of the schedule is peeled, so no MFMA runs on operands that do not
 exist: the first iteration holds K(1) Q^T and softmax(S(0)) only (there is no
@@ -167,7 +168,8 @@ class Gen(Emitter):
         self.s_t2 = 50
         self.s_m0 = 51            # m0 of the surrounding code (reserved register: saved and restored here)
         self.s_nm1 = 52           # index of the last tile
-        self.s_lk = 53            # LDS addresses of this wave's K loads, [stage][i]
+        self.s_tload = 53         # first iteration whose K load (four tiles ahead) reaches past S_kv
+        self.s_lk = 54            # LDS addresses of this wave's K loads, [stage][i]
         self.s_lv = self.s_lk + 4 * self.NLD
         self.s_last = self.s_lv + 4 * self.NLD - 1
         assert self.s_last < 100
@@ -432,7 +434,7 @@ class Gen(Emitter):
             # one test for everything rare: last iteration, masked tiles, loads that reach past S_kv
             self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))
             self.e("s_cbranch_scc1 %s" % L("SPECIAL%s_" % tag))
-        self.e("%s:" % L("TOP%s_" % tag))              # SCC: this is a special iteration (kept up to the load slots)
+        self.e("%s:" % L("TOP%s_" % tag))              # SCC: this iteration's loads reach past S_kv (kept up to the load slots)
         # loads of the previous iteration may stay in flight; everything older has landed
         if "nobar" not in self.exp:
             self.e("s_waitcnt vmcnt(%d)" % (0 if kind == "last" else 2 * self.NLD))
@@ -530,7 +532,7 @@ class Gen(Emitter):
             if kind == "loop":
                 self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_nm1))                   # the last tile?
                 self.e("s_cbranch_scc1 %s" % L("TOPL%d_" % b))
-            self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))                    # SCC = 1 again
+            self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_tload))     # SCC: do this iteration's loads need clamping?
             self.e("s_branch %s" % L("TOP%s_" % tag))
         # ---- a tile row sum failed the test: exact row maxima of the (intact) scores, move the references
         # there (alpha = exp2((m_ref - m_new) c); 0 when m_ref was still -inf), redo the tile's P, and scale
@@ -563,7 +565,7 @@ class Gen(Emitter):
         self.e("%s:" % L("KSLOW%s_" % tag))
         if "nodma" not in self.exp:
             self.dma_slow("k", b, 4)
-        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_special))                    # SCC = 1 for the V slot
+        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_tload))                      # SCC = 1 for the V slot
         self.e("s_branch %s" % L("KRET%s_" % tag))
         self.e("%s:" % L("VSLOW%s_" % tag))
         if "nodma" not in self.exp:
@@ -596,8 +598,8 @@ class Gen(Emitter):
         # first iteration that is not plain: min(first masked tile, first tile whose K load (4 tiles ahead)
         # reaches past S_kv, last tile)
         e("s_sub_i32 s%d, s%d, 1" % (self.s_nm1, self.s_ntiles))
-        e("s_sub_i32 s%d, s%d, 4" % (self.s_special, self.s_tfull))
-        e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_jmask))
+        e("s_sub_i32 s%d, s%d, 4" % (self.s_tload, self.s_tfull))
+        e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_tload, self.s_jmask))
         e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_nm1))
         e("s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kbase, 4 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kbase + 1))
