@@ -8,6 +8,7 @@
     python bench.py --probe-mfma                        # matrix-pipe ceiling: MFMA-only loop of the debug build
     python bench.py --probe-dq-atomics                  # cost of a single-pass backward's atomic dQ reduction alone
     python bench.py --timeline --config 3               # per-workgroup phase timing of one forward launch (debug build)
+    python bench.py --config 3 --compare-lib old.so     # A/B against another build of the library, same process
 
 A "step" is one attn_fwd call (the whole hot path) over one batch of seeded
 synthetic Q/K/V that is already resident in HBM.  Prints ONE JSON line.
@@ -222,9 +223,20 @@ def timeline(args, dev):
     lib.attn_fwd_trace.restype = ctypes.c_int
     lib.attn_fwd_trace.argtypes = ([ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p,
                                                                                 ctypes.c_void_p, ctypes.c_longlong])
-    cfg, q, k, v, scale = synth.make_config(args.config)
-    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
-    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    if args.paper_seq:
+        # the paper's Section 6.2 shape (bf16 here: the trace entry point takes bf16)
+        S = args.paper_seq
+        cfg = {"name": "paper_B4_H32_S%d_D128_%s_bf16" % (S, "causal" if args.causal else "full"), "B": 4, "H": 32,
+               "S_q": S, "S_kv": S, "D": 128, "causal": bool(args.causal)}
+        scale = synth.default_scale(128)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(5)
+        qd, kd, vd = [torch.randn((4, 32, S, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+                      for _ in range(3)]
+    else:
+        cfg, q, k, v, scale = synth.make_config(args.config)
+        to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
     B, H, S_q, S_kv, D = cfg["B"], cfg["H"], cfg["S_q"], cfg["S_kv"], cfg["D"]
     o = torch.empty_like(qd)
     lse = torch.empty((B, H, S_q), dtype=torch.float32, device=dev)
@@ -288,6 +300,47 @@ def timeline(args, dev):
     print(json.dumps(out), flush=True)
 
 
+def compare_lib(args, cfg, entry, qd, kd, vd, o, lse, scale, stream):
+    """The same forward call through another build of the library (say the one of an earlier commit), in this
+    process on this machine: three rounds, each timing `steps` calls of this build, then of the other (HIP events
+    per call); medians over all rounds, and whether the two builds agree bit for bit."""
+    import ctypes
+    import torch
+    def raw_call(path, o_, lse_):
+        # both builds through the bare C entry point, so that the host side of a call costs the same
+        lib = ctypes.CDLL(os.path.abspath(path))
+        fn = lib.attn_fwd_f16 if cfg["dtype"] == "f16" else lib.attn_fwd
+        fn.restype = ctypes.c_int
+        fn.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p]
+        args_ = (qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), o_.data_ptr(), lse_.data_ptr(), cfg["B"], cfg["H"],
+                 cfg["S_q"], cfg["S_kv"], cfg["D"], int(cfg["causal"]), scale, stream.cuda_stream)
+
+        def call():
+            rc = fn(*args_)
+            assert rc == 0, rc
+        return call
+    o2, lse2 = torch.empty_like(o), torch.empty_like(lse)
+    call_this = raw_call(os.path.join(ROOT, "paper_2512_18134_amd", "libmi355attn.so"), o, lse)
+    call_other = raw_call(args.compare_lib, o2, lse2)
+    times = {"this": [], "other": []}
+    for _ in range(3):
+        for name, call in (("this", call_this), ("other", call_other)):
+            for _ in range(3):
+                call()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for e0, e1 in evs:
+                e0.record(stream)
+                call()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            times[name] += [e0.elapsed_time(e1) for e0, e1 in evs]
+    this_ms, other_ms = float(np.median(times["this"])), float(np.median(times["other"]))
+    return {"lib": args.compare_lib, "this_kernel_ms_median": this_ms, "other_kernel_ms_median": other_ms,
+            "other_over_this": other_ms / this_ms,
+            "same_bits": bool(torch.equal(o.view(torch.int16), o2.view(torch.int16)) and torch.equal(lse, lse2))}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -316,6 +369,9 @@ def main():
                          "(B=1, H=8, S_q=256, S_kv=131072, D=128, non-causal; --long-skv changes S_kv)")
     ap.add_argument("--long-skv", type=int, default=131072)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--compare-lib", default="",
+                    help="also time the forward call through this other build of libmi355attn.so, interleaved "
+                         "with this build's, in the same process")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB device copy instead (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -426,6 +482,8 @@ def main():
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg["name"])},
     }
+    if args.compare_lib and not args.splitkv:
+        out["compare"] = compare_lib(args, cfg, entry, qd, kd, vd, o, lse, scale, stream)
     if not args.no_cpu_baseline:
         if q is None:  # device-generated inputs: the oracle reads the same bits back
             q, k, v = (t.cpu().view(torch.int16).numpy().view(np.uint16) for t in (qd, kd, vd))

@@ -1,8 +1,14 @@
-"""The forward kernels that load Q straight into registers do so with asm statements the compiler cannot see
+"""Checks on the compiled forward kernels (hipcc -S of csrc/attn_fwd.hip).
+
+1. The forward kernels that load Q straight into registers do so with asm statements the compiler cannot see
 into (csrc/attn_fwd_asm.h: one hand-placed s_waitcnt covers them, so that the wait for Q is not a wait for
 every K/V tile behind it).  The compiler therefore believes the destination registers are valid at once.  This
 test compiles the forward source to gfx950 assembly and follows every path from those loads: no instruction
-may touch a destination register before a vector-memory wait that covers the loads has been passed."""
+may touch a destination register before a vector-memory wait that covers the loads has been passed.
+
+2. The code around the hand-scheduled loop must not spill vector registers to scratch memory: a reload is followed
+by a wait for every load in flight, the K/V tiles of the stream included, which costs the short launches a quarter
+of their time.  (The 8-wave D = 128 loop assigns all 256 VGPRs itself; the few spills around it are known.)"""
 import os
 import re
 import subprocess
@@ -91,17 +97,44 @@ def test_checker_sees_a_planted_early_use():
     assert [s for _, s in touched_before_wait(weak)[0]] == ["v_mov_b32 v9, v5"]
 
 
-def test_no_use_of_q_registers_before_the_wait(tmp_path):
+@pytest.fixture(scope="module", params=["product", "debug"])
+def compiled(request, tmp_path_factory):
+    """Assembly text of attn_fwd.hip, built like the product library or like the debug library."""
     from paper_2512_18134_amd import build
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     if not os.path.exists(hipcc):
         pytest.skip("hipcc is not installed")
-    out = str(tmp_path / "fwd.s")
+    out = str(tmp_path_factory.mktemp(request.param) / "fwd.s")
     flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    if request.param == "debug":
+        flags.append("-DATTN_DEBUG_ENTRY_POINTS")
     src = os.path.join(ROOT, "paper_2512_18134_amd", "csrc", "attn_fwd.hip")
     subprocess.run([hipcc] + flags + ["-S", "--cuda-device-only", "-o", out, src], check=True,
                    stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
-    kernels = kernels_of(open(out).read())
+    return open(out).read()
+
+
+def test_no_scratch_around_the_hand_scheduled_loops(compiled):
+    meta = compiled[compiled.index("amdhsa.kernels:"):]
+    seen = 0
+    for block in meta.split("  - .agpr_count:")[1:]:
+        name = re.search(r"\.name:\s+(\S+)", block).group(1)
+        m = re.search(r"attn_fwd_asm_kernelILi(\d+)ELi(\d)ELi(\d)ELi(\d)E", name)
+        if not m:
+            continue
+        d, qb, sb, nw = (int(x) for x in m.groups())
+        scratch = int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", block).group(1))
+        spills = int(re.search(r"\.vgpr_spill_count:\s+(\d+)", block).group(1))
+        if d == 128 and qb == 1:
+            assert scratch <= 64, (name, scratch)      # the loop that leaves the compiler no VGPR
+        else:
+            assert scratch == 0 and spills == 0, (name, scratch, spills)
+        seen += 1
+    assert seen >= 20
+
+
+def test_no_use_of_q_registers_before_the_wait(compiled):
+    kernels = kernels_of(compiled)
     assert len(kernels) >= 20                      # every tiling, causal or not, both element types, split-KV
     with_asm_loads = 0
     for name, ins in kernels.items():
