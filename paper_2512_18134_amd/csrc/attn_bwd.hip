@@ -21,8 +21,10 @@ namespace {
 
 using attn::BwdParams;
 
+// persistent: as many workgroups as the chip holds at once, each walking the queue of owner tiles of its XCD
+// (the hand-scheduled sweeps); otherwise one workgroup per owner tile
 template <typename K>
-int launch_sweep(K kern, BwdParams p, int BH, int S_own, int NW, int lds_bytes, hipStream_t stream)
+int launch_sweep(K kern, BwdParams p, int BH, int S_own, int NW, int lds_bytes, hipStream_t stream, bool persistent = false)
 {
     p.n_t = (S_own + NW * 32 - 1) / (NW * 32);
     const long long total = (long long)BH * p.n_t;
@@ -31,7 +33,15 @@ int launch_sweep(K kern, BwdParams p, int BH, int S_own, int NW, int lds_bytes, 
     p.total_wg = (int)total;
     if (!attn::allow_lds(reinterpret_cast<const void *>(kern), lds_bytes))
         return ATTN_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)p.total_wg), dim3(NW * 64), lds_bytes, stream, p);
+    int grid = p.total_wg;
+    if (persistent) {
+        const int slots = attn::persistent_slots(reinterpret_cast<const void *>(kern), NW * 64, lds_bytes, attn::kNumXcd);
+        if (slots < attn::kNumXcd)
+            return ATTN_ERR_LAUNCH;
+        if (slots < grid)
+            grid = slots;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
@@ -53,16 +63,16 @@ int launch_bwd(const BwdParams &p, int BH, int causal, hipStream_t stream, bool 
     constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
     int rc;
     if (hand)
-        rc = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true>, p, BH, p.S_kv, 4, LDSA, stream)
-                    : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true>, p, BH, p.S_kv, 4, LDSA, stream);
+        rc = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true>, p, BH, p.S_kv, 4, LDSA, stream, true)
+                    : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true>, p, BH, p.S_kv, 4, LDSA, stream, true);
     else
         rc = causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream)
                     : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, true, NWK>, p, BH, p.S_kv, NWK, LDSK, stream);
     if (rc != ATTN_OK)
         return rc;
     if (hand)
-        return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false>, p, BH, p.S_q, 4, LDSA, stream)
-                      : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false>, p, BH, p.S_q, 4, LDSA, stream);
+        return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false>, p, BH, p.S_q, 4, LDSA, stream, true)
+                      : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false>, p, BH, p.S_q, 4, LDSA, stream, true);
     return causal ? launch_sweep(attn::attn_bwd_sweep_kernel<D, true, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream)
                   : launch_sweep(attn::attn_bwd_sweep_kernel<D, false, false, NWQ>, p, BH, p.S_q, NWQ, LDSQ, stream);
 }
@@ -199,12 +209,12 @@ static int launch_bwd_f16(const BwdParams &p, int BH, int causal, hipStream_t st
             return ATTN_ERR_LAUNCH;
     }
     constexpr int LDSA = 2 * 6 * 32 * D * 2 + 6 * 256;
-    const int rk = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true, true>, p, BH, p.S_kv, 4, LDSA, st)
-                          : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true, true>, p, BH, p.S_kv, 4, LDSA, st);
+    const int rk = causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, true, true>, p, BH, p.S_kv, 4, LDSA, st, true)
+                          : launch_sweep(attn::attn_bwd_asm_kernel<D, false, true, true>, p, BH, p.S_kv, 4, LDSA, st, true);
     if (rk != ATTN_OK)
         return rk;
-    return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false, true>, p, BH, p.S_q, 4, LDSA, st)
-                  : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false, true>, p, BH, p.S_q, 4, LDSA, st);
+    return causal ? launch_sweep(attn::attn_bwd_asm_kernel<D, true, false, true>, p, BH, p.S_q, 4, LDSA, st, true)
+                  : launch_sweep(attn::attn_bwd_asm_kernel<D, false, false, true>, p, BH, p.S_q, 4, LDSA, st, true);
 }
 
 extern "C" int attn_bwd_f16(const void *q, const void *k, const void *v, const void *o, const void *d_o,

@@ -22,10 +22,10 @@ constexpr int kW4MaxKeys = 4096;  // D = 64, causal: up to this many keys the 4-
 
 using attn::allow_lds;
 
-// wgs_per_cu: 0 = one workgroup per tile; > 0 = persistent workgroups, that many per CU, each walking the tile
-// queue of its XCD (attn_fwd_asm_kernel)
+// persistent: as many workgroups as the chip holds at once, each walking the tile queue of its XCD
+// (attn_fwd_asm_kernel); otherwise one workgroup per tile
 template <typename K>
-int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStream_t stream, int wgs_per_cu = 0)
+int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStream_t stream, bool persistent = false)
 {
     p.n_qt = (p.S_q + BM - 1) / BM;
     const long long total = (long long)BH * p.n_qt;
@@ -35,8 +35,8 @@ int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStre
     if (!allow_lds(reinterpret_cast<const void *>(kern), lds_bytes))
         return ATTN_ERR_LAUNCH;
     int grid = p.total_wg;
-    if (wgs_per_cu > 0) {
-        const int slots = attn::cu_count(attn::kNumXcd) * wgs_per_cu;
+    if (persistent) {
+        const int slots = attn::persistent_slots(reinterpret_cast<const void *>(kern), threads, lds_bytes, attn::kNumXcd);
         if (slots < attn::kNumXcd)
             return ATTN_ERR_LAUNCH;
         if (slots < grid)
@@ -56,16 +56,16 @@ int launch_simple(const Params &p, int BH, int causal, hipStream_t stream)
 }
 
 // one hand-scheduled tiling: QB 32-row query blocks per wave, SB 32-key blocks per K/V tile, NW waves; persistent
-// workgroups where the tiling has them, one per CU (two of the 4-wave D = 64 workgroups)
+// workgroups where the tiling has them
 template <int D, int QB, int SB, int NW, bool F16 = false>
 int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
 {
     typedef attn::FwdTiling<D, QB, SB, NW, false> T;
     if (causal)
         return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, true, F16>, p, BH, T::BM, NW * 64, T::LDS_BYTES, stream,
-                      T::WGS_PER_CU);
+                      T::PERSIST);
     return launch(attn::attn_fwd_asm_kernel<D, QB, SB, NW, false, F16>, p, BH, T::BM, NW * 64, T::LDS_BYTES, stream,
-                  T::WGS_PER_CU);
+                  T::PERSIST);
 }
 
 // D = 64.  w4: -1 = choose, 0 / 1 = 8-wave / 4-wave workgroups.

@@ -56,4 +56,29 @@ inline int cu_count(int multiple)
     return cached[dev] / multiple * multiple;
 }
 
+// Slots of a persistent launch of `kern` (threads per workgroup, dynamic LDS bytes as launched): compute units
+// of the current device, rounded down to a multiple of `multiple`, times the workgroups of this kernel that a CU
+// holds at once (asked from the runtime once per kernel and device).  0 when the runtime cannot tell.
+inline int persistent_slots(const void *kern, int threads, int lds_bytes, int multiple)
+{
+    constexpr int kMaxDev = 64;
+    static std::mutex mu;
+    static std::unordered_map<const void *, std::unordered_map<int, int>> cached;  // kernel -> device -> per CU
+    const int cus = cu_count(multiple);
+    int dev = 0;
+    if (cus < 1 || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev)
+        return 0;
+    std::lock_guard<std::mutex> lock(mu);
+    int &per_cu = cached[kern][dev];
+    if (per_cu == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, (size_t)lds_bytes) != hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            return 0;
+        }
+        per_cu = n;
+    }
+    return cus * per_cu;
+}
+
 }  // namespace attn

@@ -125,6 +125,9 @@ def test_no_scratch_around_the_hand_scheduled_loops(compiled):
         d, qb, sb, nw = (int(x) for x in m.groups())
         scratch = int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", block).group(1))
         spills = int(re.search(r"\.vgpr_spill_count:\s+(\d+)", block).group(1))
+        if d == 64 and nw == 4:
+            # two of these workgroups share a CU: a wave may use half a SIMD's registers (VGPRs + AGPRs)
+            assert int(re.search(r"\.vgpr_count:\s+(\d+)", block).group(1)) <= 256, name
         if d == 128 and qb == 1:
             assert scratch <= 64, (name, scratch)      # the loop that leaves the compiler no VGPR
         else:
