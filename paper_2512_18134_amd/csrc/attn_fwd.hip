@@ -426,4 +426,4 @@ extern "C" const char *attn_strerror(int status)
     return "unknown attn_status";
 }
 
-extern "C" int attn_version(void) { return 500; }
+extern "C" int attn_version(void) { return 600; }
