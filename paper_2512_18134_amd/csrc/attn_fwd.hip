@@ -68,14 +68,19 @@ int launch_asm(const Params &p, int BH, int causal, hipStream_t stream)
                   T::PERSIST);
 }
 
-// D = 64.  w4: -1 = choose, 0 / 1 = 8-wave / 4-wave workgroups.
+// D = 64.  tiling: -1 = choose, 0 = 8 waves x 32 rows (two waves per SIMD), 1 = 4 waves x 32 rows (two workgroups
+// per CU).
 // Measured: two 4-wave workgroups per CU instead of one 8-wave one change little when every workgroup
 // streams the same number of tiles (-3 % at long S, +-2 % at short S); with a causal mask and few tiles
 // the finer query tiles balance better (+13 % at S = 1024, +4 % at S = 4096).
-int launch_d64(const Params &p, int BH, int causal, hipStream_t stream, int w4 = -1)
+template <bool F16>
+int launch_d64(const Params &p, int BH, int causal, hipStream_t stream, int tiling = -1)
 {
-    const bool use4 = w4 >= 0 ? w4 != 0 : (causal && p.S_kv <= kW4MaxKeys);
-    return use4 ? launch_asm<64, 1, 2, 4>(p, BH, causal, stream) : launch_asm<64, 1, 2, 8>(p, BH, causal, stream);
+    if (tiling < 0)
+        tiling = (!F16 && causal && p.S_kv <= kW4MaxKeys) ? 1 : 0;
+    if (tiling == 1 && !F16)
+        return launch_asm<64, 1, 2, 4>(p, BH, causal, stream);
+    return launch_asm<64, 1, 2, 8, F16>(p, BH, causal, stream);
 }
 
 // D = 128.  wide: -1 = choose, 0 = 8 waves x 32 rows (two waves per SIMD), 1 = 4 waves x 64 rows (one wave
@@ -110,7 +115,7 @@ int dispatch_fwd(const Params &p, int BH, int D, int causal, hipStream_t st)
         return launch_generic(p, BH, D, causal, st);
     switch (D) {
     case 64:
-        return launch_d64(p, BH, causal, st);
+        return launch_d64<false>(p, BH, causal, st);
     case 128:
         return launch_d128<false>(p, BH, causal, st);
     default:
@@ -229,8 +234,8 @@ static int splitkv_entry(const void *q, const void *k, const void *v, void *o, f
     const int n_eff = split_plan(S_kv, n_split, p.split_len);
     if (n_eff == 1) {  // one range: the plain kernel writes o and lse itself
         if (F16)
-            return D == 64 ? launch_asm<64, 1, 2, 8, true>(p, B * H, 0, st) : launch_d128<true>(p, B * H, 0, st);
-        return D == 64 ? launch_d64(p, B * H, 0, st) : launch_d128<false>(p, B * H, 0, st);
+            return D == 64 ? launch_d64<true>(p, B * H, 0, st) : launch_d128<true>(p, B * H, 0, st);
+        return D == 64 ? launch_d64<false>(p, B * H, 0, st) : launch_d128<false>(p, B * H, 0, st);
     }
     const long long n_rows = (long long)B * H * S_q;
     p.n_split = n_eff;
@@ -271,7 +276,7 @@ extern "C" int attn_fwd_f16(const void *q, const void *k, const void *v, void *o
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (D == 256)
         return launch_asm<256, 1, 1, 4, true>(p, B * H, causal, st);
-    return D == 64 ? launch_asm<64, 1, 2, 8, true>(p, B * H, causal, st) : launch_d128<true>(p, B * H, causal, st);
+    return D == 64 ? launch_d64<true>(p, B * H, causal, st) : launch_d128<true>(p, B * H, causal, st);
 }
 
 extern "C" int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int B, int H, int S_q,
@@ -310,7 +315,7 @@ extern "C" int attn_fwd_variant(const void *q, const void *k, const void *v, voi
         return D == 128 && asm_ok ? launch_d128<false>(p, B * H, causal, st, 0) : ATTN_ERR_UNSUPPORTED;
     case 3:
     case 4:
-        return D == 64 && asm_ok ? launch_d64(p, B * H, causal, st, variant - 3) : ATTN_ERR_UNSUPPORTED;
+        return D == 64 && asm_ok ? launch_d64<false>(p, B * H, causal, st, variant - 3) : ATTN_ERR_UNSUPPORTED;
     }
     return ATTN_ERR_UNSUPPORTED;
 }

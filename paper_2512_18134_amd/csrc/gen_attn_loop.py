@@ -69,8 +69,8 @@ are re-checked on the emitted text by asm_emit.check_stream in the tests):
   * scalar write of m0 -> direct load needs 1 wait state: an s_nop goes between
     them.
 
-usage: gen_attn_loop.py <config> <out.inc> [bf16|f16] [--pfd N] [--nf N] [--w N] [--drop part,part]
-(--pfd, --nf, --w and --drop exist for timing experiments; a library build passes none)
+usage: gen_attn_loop.py <config> <out.inc> [bf16|f16] [--pfd N] [--nf N] [--w N] [--dep N] [--drop part,part]
+(--pfd, --nf, --w, --dep and --drop exist for timing experiments; a library build passes none)
 """
 import os
 import struct
@@ -92,7 +92,7 @@ CONFIGS = {
 
 
 class Gen(Emitter):
-    def __init__(self, name, dtype="bf16", NF=None, PFD=None, W=None, drop=()):
+    def __init__(self, name, dtype="bf16", NF=None, PFD=None, W=None, drop=(), DEP=None):
         Emitter.__init__(self)
         cfg = CONFIGS[name]
         NF = cfg["NF"] if NF is None else NF
@@ -123,8 +123,10 @@ class Gen(Emitter):
         # ---- register map
         v = [0]
         a = [0]
-        def take(n, agpr=False):
+        def take(n, agpr=False, operand=False):
             c = a if agpr else v
+            if operand and n > 1:
+                c[0] += c[0] & 1      # a register tuple bound to a C++ operand starts at an even register
             b = c[0]
             c[0] += n
             return b
@@ -140,14 +142,15 @@ class Gen(Emitter):
         self.DVOFF = take(self.NLD)
         self.DROW = take(self.NLD)
         self.DCH = take(self.NLD)
-        self.MREF = take(QB)
+        self.MREF = take(QB, operand=True)
         self.MRC = take(QB)
-        self.L = take(QB)                 # running row sums (this lane's half of the keys)
+        self.L = take(QB, operand=True)   # running row sums (this lane's half of the keys)
         self.TLA = take(QB)               # row sums of the current tile, two partial sums each
         self.TLB = take(QB)
-        self.TP = take(8)                 # exponent / exp temporaries: four element pairs (three in flight)
+        self.DEP = cfg.get("DEP", 1) if DEP is None else DEP   # element pairs between fma, exp2 and the add / pack
+        self.TP = take(2 * (2 * self.DEP + 2))   # exponent / exp temporaries: 2 DEP + 1 element pairs in flight, one kept
         self.ALPHA = take(QB)
-        self.THRB = take(QB)
+        self.THRB = take(QB, operand=True)
         self.THR = take(QB)
         self.T = take(QB)
         self.TMP2 = take(QB)
@@ -249,13 +252,14 @@ class Gen(Emitter):
         The exponent arguments go to the temporaries TP: S_cur stays intact for the out-of-line pass."""
         pairs = self.pairs()
         def tp(t, i):
-            return self.TP + 2 * (t % 4) + i
+            return self.TP + 2 * (t % (2 * self.DEP + 2)) + i
         def F(t):
             qb = pairs[t][0]
             return ["v_fma_f32 v%d, v%d, s%d, -v%d" % (tp(t, i), x, self.s_c, self.MRC + qb)
                     for i, x in enumerate(self.pair_regs(S_cur, pairs[t]))]
         def E(t):
-            return ["v_exp_f32 v%d, v%d" % (tp(t, i), tp(t, i)) for i in (0, 1)]
+            op = "v_mov_b32" if "noexp" in self.exp else "v_exp_f32"     # timing experiment: a full-rate stand-in
+            return ["%s v%d, v%d" % (op, tp(t, i), tp(t, i)) for i in (0, 1)]
         def A(t):
             qb, k = pairs[t]
             if k == 0:     # the partial sums of a query block start with its first two pairs (next step)
@@ -271,13 +275,13 @@ class Gen(Emitter):
             return []
         ops = []
         n = len(pairs)
-        for t in range(n + 2):
+        for t in range(n + 2 * self.DEP):
             if t < n:
                 ops += F(t)
-            if 0 <= t - 1 < n:
-                ops += E(t - 1)
-            if 0 <= t - 2 < n:
-                ops += A(t - 2)
+            if 0 <= t - self.DEP < n:
+                ops += E(t - self.DEP)
+            if 0 <= t - 2 * self.DEP < n:
+                ops += A(t - 2 * self.DEP)
         for qb in range(self.QB):
             ops.append("v_add_f32 v%d, v%d, v%d" % (self.TLA + qb, self.TLA + qb, self.TLB + qb))
         if self.QB == 2:   # the sum of two positive sums is below the bound only if both are; inf / NaN carry over
@@ -287,7 +291,7 @@ class Gen(Emitter):
     def check_ops(self, tag):
         """Tile row sums below the bound?  Otherwise (too large, inf or NaN) take the out-of-line pass."""
         if "novalu" in self.exp:
-            return []
+            return ["%s:" % self.lab("SLOWRET%s_" % tag)]
         ts = self.TS if self.QB == 2 else self.TLA
         ops = ["v_cmp_ngt_f32 vcc, s%d, v%d" % (self.s_tau, ts),     # not (bound > sum)
                "s_cbranch_vccnz %s" % self.lab("SLOW%s_" % tag),
@@ -452,7 +456,7 @@ class Gen(Emitter):
                 "s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vptr + 1),
                 "s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j)]
             if "nodma" in self.exp:
-                extra[0], extra[1] = [], []
+                extra[0], extra[1] = ["%s:" % L("KRET%s_" % tag)], ["%s:" % L("VRET%s_" % tag)]
         # ---- VALU program: dealt out so that every slot carries about the same issue cost
         b_ops = self.pair_ops(S_cur, P_new)
         # sum of the K Q^T partial accumulators: in the last slots of a loop iteration (its K Q^T ends in the
@@ -691,13 +695,15 @@ class Gen(Emitter):
 def main(argv):
     args = list(argv)
     kw = {}
-    while len(args) > 2 and args[-2] in ("--pfd", "--nf", "--w", "--drop"):
+    while len(args) > 2 and args[-2] in ("--pfd", "--nf", "--w", "--drop", "--dep"):
         if args[-2] == "--pfd":
             kw["PFD"] = int(args[-1])
         elif args[-2] == "--nf":
             kw["NF"] = int(args[-1])
         elif args[-2] == "--w":
             kw["W"] = int(args[-1])
+        elif args[-2] == "--dep":
+            kw["DEP"] = int(args[-1])
         else:
             kw["drop"] = tuple(filter(None, args[-1].split(",")))
         args = args[:-2]

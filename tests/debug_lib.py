@@ -8,6 +8,7 @@ _ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PATH = os.path.join(_ROOT, "paper_2512_18134_amd", "libmi355attn_debug.so")
 
 FWD_AS_DISPATCHED, FWD_PROGRAM_ORDER, FWD_D128_ONE_WAVE_PER_SIMD, FWD_D64_8_WAVES, FWD_D64_4_WAVES = range(5)
+FWD_D128_TWO_WAVES_PER_SIMD = 5
 ATTN_ERR_UNSUPPORTED = -7
 
 _lib = None

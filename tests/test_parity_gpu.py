@@ -298,13 +298,14 @@ def test_pipelined_schedule_equals_program_order_kernel(B):
 
 
 def test_tiling_variants_agree_with_the_oracle(B):
-    # the tilings that attn_fwd picks by shape (D = 64: 8-wave or 4-wave workgroups) and the D = 128
-    # one-wave-per-SIMD tiling, each forced through the debug build on a shape the dispatcher would give
-    # to another one
+    # every tiling the library holds for D = 64 and D = 128, each forced through the debug build (also on
+    # shapes the dispatcher would give to another one)
     import debug_lib
     for D, causal, variant in ((64, True, debug_lib.FWD_D64_8_WAVES), (64, False, debug_lib.FWD_D64_4_WAVES),
                                (128, True, debug_lib.FWD_D128_ONE_WAVE_PER_SIMD),
-                               (128, False, debug_lib.FWD_D128_ONE_WAVE_PER_SIMD)):
+                               (128, False, debug_lib.FWD_D128_ONE_WAVE_PER_SIMD),
+                               (128, True, debug_lib.FWD_D128_TWO_WAVES_PER_SIMD),
+                               (128, False, debug_lib.FWD_D128_TWO_WAVES_PER_SIMD)):
         q, k, v = synth.make_qkv(2, 2, 530, 610, D, seed=37)
         scale = synth.default_scale(D)
         o, lse = debug_lib.attn_fwd_variant(to_dev(q), to_dev(k), to_dev(v), causal, scale, variant)
