@@ -56,8 +56,9 @@ typedef enum attn_status {
  *
  * Ownership: the caller owns all five buffers and keeps them alive until the
  * work enqueued on `stream` has completed.  The library allocates nothing,
- * keeps no state between calls that changes a result (it remembers only that a
- * kernel's launch attribute has been set) and never synchronises the device.  o/lse must
+ * keeps no state between calls that changes a result (it remembers only, per
+ * kernel and device, that a launch attribute has been set and how many workgroups
+ * the chip holds at once) and never synchronises the device.  o/lse must
  * not overlap q/k/v.
  *
  * Errors: arguments are validated on the host before any HIP call; on a
@@ -65,7 +66,7 @@ typedef enum attn_status {
  * launched.  A launch the runtime rejects returns ATTN_ERR_LAUNCH.  The
  * function never aborts or throws.  NaN/Inf inside q, k, v are not checked
  * (the outputs are then unspecified).  Results are bitwise reproducible from
- * run to run (no atomics).
+ * run to run (no atomics; workgroups take tiles in a fixed order).
  */
 int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
              int B, int H, int S_q, int S_kv, int D, int causal, float scale,
