@@ -13,7 +13,8 @@ tile of 32 rows = NM MFMA slots, schedule length 3 I): iteration j issues, from 
     S and dP MFMAs of tile j+1
     contraction MFMAs of tile j-1, second half
     next to:  the VALU work of tile j  (x = S c - LSE', t = dP - Delta, p = exp2 x, ds = p t,
-              bf16 packs), dealt out over the MFMA slots; LDS operand reads PFD slots ahead.
+              bf16 packs), dealt out over the MFMA slots so that every slot carries about the same
+              issue cost (asm_emit.spread); LDS operand reads PFD slots ahead.
 
 Registers are assigned here: the accumulators and the owner's K/V (or Q/dO) rows, which only the
 matrix pipe touches, live in AGPRs; S, dP, P, dS and all addresses in VGPRs.  Streamed tiles
@@ -37,7 +38,7 @@ import os
 import sys
 
 sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
-from asm_emit import Emitter  # noqa: E402
+from asm_emit import Emitter, spread  # noqa: E402
 
 
 # (key owner?, D) -> NF: fragment buffers; PFD: MFMA slots between a fragment's LDS read and its use;
@@ -51,7 +52,8 @@ DEFAULTS = {
 
 
 class Gen(Emitter):
-    def __init__(self, key_owner, D, NF=None, PFD=None, dtype="bf16", drop=(), W=None):
+    def __init__(self, key_owner, D, NF=None, PFD=None, dtype="bf16", drop=(), W=None, balance=True):
+        self.balance = balance
         Emitter.__init__(self)
         assert D in (64, 128) and dtype in ("bf16", "f16")
         dflt = DEFAULTS[(bool(key_owner), D)]
@@ -315,6 +317,24 @@ class Gen(Emitter):
         n2 = NM - n1
         for i in range(n2):
             valu[n1 + i] = p2[i * len(p2) // n2:(i + 1) * len(p2) // n2]
+        if self.balance:
+            # deal the two phases out by issue cost instead of by count: a slot's MFMA, its s_waitcnt, the LDS
+            # reads and scalar work it carries count against its share of the VALU program
+            grps = self.groups()
+            def fixed_of(lo, hi):
+                out = {}
+                for slot in range(lo, hi):
+                    c = 1.0 + (1.0 if slot % self.W == 0 else 0.0)
+                    c += len(self.frag_loads(grps[(slot + self.PFD) % NM], 0, 0, 0))
+                    c += {0: 2 + 6 * self.NLD, 1: 7 if self.KO else 0, 2: 6}.get(slot, 0)
+                    if self.KO and slot == n1:
+                        c += 8
+                    out[slot - lo] = c
+                return out
+            a = spread(p1, fixed_of(0, n1), n1)
+            b2 = spread(p2, fixed_of(n1, NM), n2)
+            valu = {i: a[i] for i in range(n1)}
+            valu.update({n1 + i: b2[i] for i in range(n2)})
         lds = {}
         if self.KO:
             lds[n1] = self.aux_reads(rst)       # after the last use of this tile's values
@@ -468,21 +488,24 @@ class Gen(Emitter):
 
 
 if __name__ == "__main__":
-    # --nf / --pfd / --w / --drop: timing experiments (fragment buffers, prefetch distance, groups per wait, parts left out);
+    # --nf / --pfd / --w / --balance / --drop: timing experiments (fragment buffers, prefetch distance, groups per wait,
+    # VALU program dealt out by count instead of by cost, parts left out);
     # a library build passes none of them
     args = sys.argv[1:]
-    nf, pfd, w, drop = None, None, None, ()
-    while len(args) > 3 and args[-2] in ("--nf", "--pfd", "--w", "--drop"):
+    nf, pfd, w, drop, balance = None, None, None, (), True
+    while len(args) > 3 and args[-2] in ("--nf", "--pfd", "--w", "--drop", "--balance"):
         if args[-2] == "--nf":
             nf = int(args[-1])
         elif args[-2] == "--pfd":
             pfd = int(args[-1])
         elif args[-2] == "--w":
             w = int(args[-1])
+        elif args[-2] == "--balance":
+            balance = bool(int(args[-1]))
         else:
             drop = tuple(filter(None, args[-1].split(",")))
         args = args[:-2]
     dtype = args[3] if len(args) > 3 else "bf16"
-    text = Gen(args[0] == "kv", int(args[1]), NF=nf, PFD=pfd, dtype=dtype, drop=drop, W=w).emit_inc()
+    text = Gen(args[0] == "kv", int(args[1]), NF=nf, PFD=pfd, dtype=dtype, drop=drop, W=w, balance=balance).emit_inc()
     with open(args[2], "w") as f:
         f.write(text)
