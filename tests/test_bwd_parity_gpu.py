@@ -93,6 +93,22 @@ def test_small_shapes_elementwise(B, shape):
     compare(got, want, str(shape))
 
 
+@pytest.mark.parametrize("shape", [(1, 3, 100, 128 * 101 + 5, 128, False), (1, 3, 128 * 90 + 3, 64, 128, True),
+                                   (1, 5, 150, 128 * 120 + 77, 64, False), (2, 2, 128 * 150 + 1, 96, 64, True)],
+                         ids=lambda s: "B%d_H%d_Sq%d_Skv%d_D%d_%s" % (s[0], s[1], s[2], s[3], s[4], "causal" if s[5] else "full"))
+def test_more_owner_tiles_than_cu_slots(B, shape):
+    # one of the two sweeps has more owner tiles than the chip has workgroup slots (and the other only a few):
+    # its persistent workgroups walk their queues through several passes, the last one short
+    b, h, sq, skv, d, causal = shape
+    print("bwd case", shape, flush=True)
+    q, k, v = synth.make_qkv(b, h, sq, skv, d, seed=900 + d)
+    d_o = synth.make_do(b, h, sq, d, seed=900 + d)
+    scale = synth.default_scale(d)
+    got = run_gpu(B, q, k, v, d_o, causal, scale)
+    want = attn_bwd_ref(q, k, v, d_o, causal, scale)
+    compare(got, want, str(shape))
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_sharp_softmax(B, d):
     b, h, s = 1, 2, 600
