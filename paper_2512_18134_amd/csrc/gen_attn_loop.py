@@ -618,6 +618,9 @@ class Gen(Emitter):
             e("v_mov_b32 v%d, 0xff800000" % (self.MREF + qb))        # no reference yet: the first tile's test fails
             e("v_mov_b32 v%d, 0xff800000" % (self.MRC + qb))
             e("v_mov_b32 v%d, 0" % (self.L + qb))
+        if "nolds" in self.exp:      # timing experiment: the fragments are never read; keep them finite
+            for r in range(4 * self.NF):
+                e("v_mov_b32 v%d, 0" % (self.FR + r))
         self.body(0, "first")
         for b in range(4):
             self.body(b)
