@@ -35,10 +35,9 @@ int launch_sweep(K kern, BwdParams p, int BH, int S_own, int NW, int lds_bytes, 
         return ATTN_ERR_LAUNCH;
     int grid = p.total_wg;
     if (persistent) {
+        // (a runtime that cannot tell the occupancy gets one workgroup per owner tile: the kernel takes either)
         const int slots = attn::persistent_slots(reinterpret_cast<const void *>(kern), NW * 64, lds_bytes, attn::kNumXcd);
-        if (slots < attn::kNumXcd)
-            return ATTN_ERR_LAUNCH;
-        if (slots < grid)
+        if (slots >= attn::kNumXcd && slots < grid)
             grid = slots;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds_bytes, stream, p);

@@ -36,10 +36,9 @@ int launch(K kern, Params p, int BH, int BM, int threads, int lds_bytes, hipStre
         return ATTN_ERR_LAUNCH;
     int grid = p.total_wg;
     if (persistent) {
+        // (a runtime that cannot tell the occupancy gets one workgroup per tile: the kernel takes either)
         const int slots = attn::persistent_slots(reinterpret_cast<const void *>(kern), threads, lds_bytes, attn::kNumXcd);
-        if (slots < attn::kNumXcd)
-            return ATTN_ERR_LAUNCH;
-        if (slots < grid)
+        if (slots >= attn::kNumXcd && slots < grid)
             grid = slots;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds_bytes, stream, p);
