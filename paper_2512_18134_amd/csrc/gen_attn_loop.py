@@ -87,14 +87,16 @@ CONFIGS = {
     "d64_w4": dict(D=64,  QB=1, SB=2, NW=4, AG=False, NACC=1, NF=8, PFD=6, W=2),
     "d128":   dict(D=128, QB=1, SB=2, NW=8, AG=False, NACC=1, NF=4, PFD=3, W=1),
     "d128a":  dict(D=128, QB=2, SB=1, NW=4, AG=True,  NACC=1, NF=8, PFD=7, W=4),
-    "d256a":  dict(D=256, QB=1, SB=1, NW=4, AG=True,  NACC=2, NF=8, PFD=7, W=4),
+    "d256a":  dict(D=256, QB=1, SB=1, NW=4, AG=True,  NACC=2, NF=8, PFD=7, W=4, LS=2),
 }
 
 
 class Gen(Emitter):
-    def __init__(self, name, dtype="bf16", NF=None, PFD=None, W=None, drop=(), DEP=None):
+    def __init__(self, name, dtype="bf16", NF=None, PFD=None, W=None, drop=(), DEP=None, LS=None):
         Emitter.__init__(self)
         cfg = CONFIGS[name]
+        # direct loads of an iteration: LS = 0: K's in slot 0, V's in slot 1; LS > 0: one load per slot, LS slots apart
+        self.LS = cfg.get("LS", 0) if LS is None else LS
         NF = cfg["NF"] if NF is None else NF
         PFD = cfg["PFD"] if PFD is None else PFD
         self.W = cfg["W"] if W is None else W
@@ -447,15 +449,31 @@ class Gen(Emitter):
         # (nothing between the test above and these two branches writes SCC), pointer bumps in slot 2
         extra = {}
         if kind != "last":
-            extra[0] = ["s_cbranch_scc1 %s" % L("KSLOW%s_" % tag)] + self.dma_fast("k", b) + ["%s:" % L("KRET%s_" % tag)]
-            extra[1] = ["s_cbranch_scc1 %s" % L("VSLOW%s_" % tag)] + self.dma_fast("v", (b + 2) % 4) + ["%s:" % L("VRET%s_" % tag)]
-            extra[2] = [
+            bumps = [
                 "s_add_u32 s%d, s%d, %d" % (self.s_kptr, self.s_kptr, self.TB),
                 "s_addc_u32 s%d, s%d, 0" % (self.s_kptr + 1, self.s_kptr + 1),
                 "s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vptr, self.TB),
                 "s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vptr + 1),
                 "s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j)]
+            if self.LS == 0:
+                extra[0] = ["s_cbranch_scc1 %s" % L("KSLOW%s_" % tag)] + self.dma_fast("k", b) + ["%s:" % L("KRET%s_" % tag)]
+                extra[1] = ["s_cbranch_scc1 %s" % L("VSLOW%s_" % tag)] + self.dma_fast("v", (b + 2) % 4) + ["%s:" % L("VRET%s_" % tag)]
+                extra[2] = bumps
+            else:
+                # one load per slot: a wave that issues several in a row waits for the address unit to take
+                # them.  The out-of-line clamped loads (all of K and V at once, from the first load slot) come
+                # back with SCC still set, which sends the other slots past their loads.
+                one = [self.dma_fast("k", b)[3 * i:3 * i + 3] for i in range(self.NLD)] + \
+                      [self.dma_fast("v", (b + 2) % 4)[3 * i:3 * i + 3] for i in range(self.NLD)]
+                ls = min(self.LS, (n_soft - 2) // (len(one) - 1))      # the first iteration has fewer slots
+                assert ls >= 1
+                for n, ld in enumerate(one):
+                    lab = L(("KRET%s_" if n == 0 else "LD%d_%%s_" % n) % tag)
+                    to = L("KSLOW%s_" % tag) if n == 0 else lab
+                    extra[n * ls] = ["s_cbranch_scc1 %s" % to] + ld + ["%s:" % lab]
+                extra[(len(one) - 1) * ls + 1] = bumps
             if "nodma" in self.exp:
+                assert self.LS == 0
                 extra[0], extra[1] = ["%s:" % L("KRET%s_" % tag)], ["%s:" % L("VRET%s_" % tag)]
         # ---- VALU program: dealt out so that every slot carries about the same issue cost
         b_ops = self.pair_ops(S_cur, P_new)
@@ -569,8 +587,12 @@ class Gen(Emitter):
         self.e("%s:" % L("KSLOW%s_" % tag))
         if "nodma" not in self.exp:
             self.dma_slow("k", b, 4)
-        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_tload))                      # SCC = 1 for the V slot
+        if self.LS:
+            self.dma_slow("v", (b + 2) % 4, 2)
+        self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_tload))     # SCC = 1 for the load slots that follow
         self.e("s_branch %s" % L("KRET%s_" % tag))
+        if self.LS:
+            return
         self.e("%s:" % L("VSLOW%s_" % tag))
         if "nodma" not in self.exp:
             self.dma_slow("v", (b + 2) % 4, 2)
@@ -698,7 +720,7 @@ class Gen(Emitter):
 def main(argv):
     args = list(argv)
     kw = {}
-    while len(args) > 2 and args[-2] in ("--pfd", "--nf", "--w", "--drop", "--dep"):
+    while len(args) > 2 and args[-2] in ("--pfd", "--nf", "--w", "--drop", "--dep", "--ls"):
         if args[-2] == "--pfd":
             kw["PFD"] = int(args[-1])
         elif args[-2] == "--nf":
@@ -707,6 +729,8 @@ def main(argv):
             kw["W"] = int(args[-1])
         elif args[-2] == "--dep":
             kw["DEP"] = int(args[-1])
+        elif args[-2] == "--ls":
+            kw["LS"] = int(args[-1])
         else:
             kw["drop"] = tuple(filter(None, args[-1].split(",")))
         args = args[:-2]

@@ -41,6 +41,14 @@ def test_forward_main_path_twice_round(name, dtype):
     assert asm_emit.check_stream(path) == len(path)
 
 
+def clamped_loads(g, tag):
+    """Branches an iteration takes when its loads are the clamped ones: out of line from the first load slot
+    (all of them at once when every load has a slot of its own, K then V otherwise), past the other slots."""
+    if g.LS == 0:
+        return ["KSLOW%s_" % tag, "VSLOW%s_" % tag]
+    return ["KSLOW%s_" % tag] + ["LD%d_%s_" % (n, tag) for n in range(1, 2 * g.NLD)]
+
+
 @pytest.mark.parametrize("name", list(gen_attn_loop.CONFIGS))
 @pytest.mark.parametrize("b", range(4))
 def test_forward_out_of_line_sections(name, b):
@@ -48,8 +56,8 @@ def test_forward_out_of_line_sections(name, b):
     g = gen_attn_loop.Gen(name)
     # each detour is taken the first time its branch is met (body b of the first round; the bodies are
     # alike, so b = 1..3 also cover a detour with loop-carried state before it), then the loop goes on
-    for detour in (["SLOW%d_" % b], ["SPECIAL%d_" % b, "KSLOW%d_" % b, "VSLOW%d_" % b],
-                   ["SPECIAL%d_" % b, "NOMASK%d_" % b, "KSLOW%d_" % b, "VSLOW%d_" % b]):
+    for detour in (["SLOW%d_" % b], ["SPECIAL%d_" % b] + clamped_loads(g, b),
+                   ["SPECIAL%d_" % b, "NOMASK%d_" % b] + clamped_loads(g, b)):
         path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=2)
         assert asm_emit.check_stream(path) == len(path)
         assert sum(1 for l in path if l.startswith("v_mfma")) == g.NQKG * g.QB + 11 * g.NM
@@ -69,14 +77,43 @@ def test_forward_out_of_line_sections(name, b):
 def test_forward_first_iteration_and_single_tile(name):
     lines = fwd_lines(name)
     g = gen_attn_loop.Gen(name)
-    for detour in (["SLOWF_"], ["SPECIALF_", "KSLOWF_", "VSLOWF_"], ["SPECIALF_", "NOMASKF_", "KSLOWF_", "VSLOWF_"]):
+    for detour in (["SLOWF_"], ["SPECIALF_"] + clamped_loads(g, "F"), ["SPECIALF_", "NOMASKF_"] + clamped_loads(g, "F")):
         path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=1)
         assert asm_emit.check_stream(path) == len(path)
     # a launch with one tile: the first iteration (its loads clamped), then straight to P(0) V(0)
-    path = asm_emit.walk(lines, take=["SPECIALF_", "SLOWF_", "KSLOWF_", "VSLOWF_", "SPECIAL1_", "EXIT1_"])
+    path = asm_emit.walk(lines, take=["SPECIALF_", "SLOWF_"] + clamped_loads(g, "F") + ["SPECIAL1_", "EXIT1_"])
     assert asm_emit.check_stream(path) == len(path)
     assert sum(1 for l in path if l.startswith("v_mfma")) == (g.NQKG + g.NPVG) * g.QB
     assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
+
+
+@pytest.mark.parametrize("name", list(gen_attn_loop.CONFIGS))
+def test_forward_load_slots_see_the_flag_the_iteration_started_with(name):
+    """SCC is set once per iteration (loads reach past S_kv or not) and read by every load slot: nothing
+    between the top of the iteration and the last load slot may write it, every path issues each of the
+    iteration's 2 NLD direct loads exactly once, and the out-of-line loads come back with the flag set."""
+    lines = [l.strip() for l in fwd_lines(name)]
+    g = gen_attn_loop.Gen(name)
+    keeps_scc = ("s_waitcnt", "s_nop", "s_barrier", "s_mov_b32", "s_cbranch_scc1")
+    for tag in ("F", "0", "1", "2", "3"):
+        top = lines.index("TOP%s_:" % tag)
+        slot_labels = ["KRET%s_:" % tag] + (["VRET%s_:" % tag] if g.LS == 0 else
+                                            ["LD%d_%s_:" % (n, tag) for n in range(1, 2 * g.NLD)])
+        end = max(lines.index(l) for l in slot_labels)
+        region = [l for l in lines[top:end] if not l.endswith(":")]
+        for l in region:
+            assert not l.startswith("s_") or l.split()[0] in keeps_scc, l
+        assert sum(l.startswith("s_cbranch_scc1") for l in region) == len(slot_labels)
+        assert sum(l.startswith("global_load_lds") for l in region) == 2 * g.NLD
+        # the clamped loads: one iteration through them, counted between its barrier and the next
+        path = asm_emit.walk(lines, take=["SPECIAL%s_" % tag] + clamped_loads(g, tag), loop_label="BODY0_", loop_visits=2)
+        slow = lines.index("KSLOW%s_:" % tag)
+        k = next(i for i, l in enumerate(path) if l == lines[slow + 1] and path[i:i + 3] == lines[slow + 1:slow + 4])
+        before = max(i for i in range(k) if path[i] == "s_barrier")
+        after = min(i for i in range(k, len(path)) if path[i] == "s_barrier" or i == len(path) - 1)
+        assert sum(l.startswith("global_load_lds") for l in path[before:after]) == 2 * g.NLD
+        ret = lines.index("s_branch KRET%s_" % tag, slow)
+        assert lines[ret - 1].startswith("s_cmp_ge_i32 s%d, s%d" % (g.s_j, g.s_tload))
 
 
 BWD = [(ko, d, dt) for ko in (True, False) for d in (64, 128) for dt in ("bf16", "f16")]
