@@ -174,9 +174,10 @@ class Gen(Emitter):
         self.s_m0 = 51            # m0 of the surrounding code (reserved register: saved and restored here)
         self.s_nm1 = 52           # index of the last tile
         self.s_tload = 53         # first iteration whose K load (four tiles ahead) reaches past S_kv
-        self.s_lk = 54            # LDS addresses of this wave's K loads, [stage][i]
-        self.s_lv = self.s_lk + 4 * self.NLD
-        self.s_last = self.s_lv + 4 * self.NLD - 1
+        self.s_lk = 54            # LDS addresses of this wave's K loads, [stage] (load i: + i KB, an immediate)
+        self.s_lv = self.s_lk + 4
+        self.s_last = self.s_lv + 4 - 1
+        assert self.NLD <= 4      # the immediate offset of a load ends at 4095
         assert self.s_last < 100
 
     # ------------------------------------------------------------------ helpers
@@ -373,18 +374,22 @@ class Gen(Emitter):
 
     # ------------------------------------------------------------------- DMA
     def dma_fast(self, which, stage):
-        """One K or V tile: NLD x (m0 <- LDS address, s_nop, direct load); the scalar base already points at
-        the tile.  The wait state between the m0 write and the load has to be an s_nop: with a VALU
-        instruction of the softmax program in its place that instruction's result came out wrong on the
-        MI355X (measured; every other use of the slot stayed correct)."""
+        """One K or V tile, as a list of NLD instruction groups (one direct load each): m0 <- LDS address of
+        the wave's NLD KB of the stage, s_nop, then load i with the immediate offset i KB, which the hardware
+        adds to the LDS address and to the global address alike (the offset register of load i holds i KB
+        less to make up for it); the scalar base already points at the tile.  The wait state between the m0
+        write and the first load has to be an s_nop: with a VALU instruction of the softmax program in its
+        place that instruction's result came out wrong on the MI355X (measured; every other use of the slot
+        stayed correct).  Nothing else in the loop writes m0 between the loads of a tile."""
         tab = self.s_lk if which == "k" else self.s_lv
         ptr = self.s_kptr if which == "k" else self.s_vptr
-        out = []
         if "nodma" in self.exp:
-            return out
+            return [[] for _ in range(self.NLD)]
+        out = []
         for i in range(self.NLD):
-            out += ["s_mov_b32 m0, s%d" % (tab + stage * self.NLD + i), "s_nop 0",
-                    "global_load_lds_dwordx4 v%d, %s" % (self.DVOFF + i, self.sr(ptr, 2))]
+            head = ["s_mov_b32 m0, s%d" % (tab + stage), "s_nop 0"] if i == 0 else []
+            out.append(head + ["global_load_lds_dwordx4 v%d, %s%s" % (self.DVOFF + i, self.sr(ptr, 2),
+                                                                     " offset:%d" % (1024 * i) if i else "")])
         return out
 
     def dma_slow(self, which, stage, ahead):
@@ -399,7 +404,7 @@ class Gen(Emitter):
             self.e("v_add_u32 v%d, s%d, v%d" % (t, self.s_t2, self.DROW + i))
             self.e("v_min_i32 v%d, s%d, v%d" % (t, self.s_skvm1, t))
             self.e("v_lshlrev_b32 v%d, %d, v%d" % (t, sh, t))
-            self.e("s_mov_b32 m0, s%d" % (tab + stage * self.NLD + i))
+            self.e(("s_add_u32 m0, s%d, %d" % (tab + stage, 1024 * i)) if i else ("s_mov_b32 m0, s%d" % (tab + stage)))
             self.e("v_add_u32 v%d, v%d, v%d" % (t, t, self.DCH + i))
             self.e("s_nop 0")
             self.e("global_load_lds_dwordx4 v%d, %s" % (t, self.sr(base, 2)))
@@ -456,15 +461,14 @@ class Gen(Emitter):
                 "s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vptr + 1),
                 "s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j)]
             if self.LS == 0:
-                extra[0] = ["s_cbranch_scc1 %s" % L("KSLOW%s_" % tag)] + self.dma_fast("k", b) + ["%s:" % L("KRET%s_" % tag)]
-                extra[1] = ["s_cbranch_scc1 %s" % L("VSLOW%s_" % tag)] + self.dma_fast("v", (b + 2) % 4) + ["%s:" % L("VRET%s_" % tag)]
+                extra[0] = ["s_cbranch_scc1 %s" % L("KSLOW%s_" % tag)] + sum(self.dma_fast("k", b), []) + ["%s:" % L("KRET%s_" % tag)]
+                extra[1] = ["s_cbranch_scc1 %s" % L("VSLOW%s_" % tag)] + sum(self.dma_fast("v", (b + 2) % 4), []) + ["%s:" % L("VRET%s_" % tag)]
                 extra[2] = bumps
             else:
                 # one load per slot: a wave that issues several in a row waits for the address unit to take
                 # them.  The out-of-line clamped loads (all of K and V at once, from the first load slot) come
                 # back with SCC still set, which sends the other slots past their loads.
-                one = [self.dma_fast("k", b)[3 * i:3 * i + 3] for i in range(self.NLD)] + \
-                      [self.dma_fast("v", (b + 2) % 4)[3 * i:3 * i + 3] for i in range(self.NLD)]
+                one = self.dma_fast("k", b) + self.dma_fast("v", (b + 2) % 4)
                 ls = min(self.LS, (n_soft - 2) // (len(one) - 1))      # the first iteration has fewer slots
                 assert ls >= 1
                 for n, ld in enumerate(one):
@@ -632,10 +636,8 @@ class Gen(Emitter):
         e("s_add_u32 s%d, s%d, %d" % (self.s_vptr, self.s_vbase, 2 * self.TB))
         e("s_addc_u32 s%d, s%d, 0" % (self.s_vptr + 1, self.s_vbase + 1))
         for st in range(4):
-            for i in range(self.NLD):
-                off = st * self.TB + i * self.NW * 1024
-                e("s_add_u32 s%d, s%d, %d" % (self.s_lk + st * self.NLD + i, self.s_ldsk, off))
-                e("s_add_u32 s%d, s%d, %d" % (self.s_lv + st * self.NLD + i, self.s_ldsv, off))
+            e("s_add_u32 s%d, s%d, %d" % (self.s_lk + st, self.s_ldsk, st * self.TB))
+            e("s_add_u32 s%d, s%d, %d" % (self.s_lv + st, self.s_ldsv, st * self.TB))
         for qb in range(QB):
             e("v_mov_b32 v%d, 0xff800000" % (self.MREF + qb))        # no reference yet: the first tile's test fails
             e("v_mov_b32 v%d, 0xff800000" % (self.MRC + qb))

@@ -444,12 +444,12 @@ def paper_toy():
 #     per product;
 #   * on all-zero inputs (chip not power limited) the one-wave-per-SIMD loop keeps the pipe busy 81.5 % of
 #     the cycles while it issues GFX950_STREAM_INSTRS instructions per 32 MFMAs: the wave's issue port is
-#     the binding unit there, at 32 * 32 / 0.815 / 198 = 6.3 cycles per instruction on average;
+#     the binding unit there, at 32 * 32 / 0.815 / 194 = 6.5 cycles per instruction on average;
 #   * the softmax of a tile is GFX950_SOFTMAX_INSTRS of those instructions, the LDS operand reads 16 + 32
 #     (8 + 16 when a fragment feeds two MFMAs).
 GFX950_MFMA_CYCLES = 32
 GFX950_UNTHROTTLED_BUSY = 0.815
-GFX950_STREAM_INSTRS = 198
+GFX950_STREAM_INSTRS = 194
 GFX950_SOFTMAX_INSTRS = 114
 GFX950_ISSUE_CYCLES = GFX950_MFMA_CYCLES * 32 / GFX950_UNTHROTTLED_BUSY / GFX950_STREAM_INSTRS
 GFX950_D128 = {"QK": 16 * GFX950_MFMA_CYCLES, "SM": round(GFX950_SOFTMAX_INSTRS * GFX950_ISSUE_CYCLES),
