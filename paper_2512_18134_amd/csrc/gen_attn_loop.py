@@ -212,7 +212,7 @@ class Gen(Emitter):
         """LDS reads that bring the A operand of group `grp` into fragment buffer `buf`."""
         f = self.FR + 4 * buf
         kind, a, b = grp
-        if "nolds" in self.exp:
+        if "nolds" in self.exp or "ldsonce" in self.exp:
             return []
         if kind == "pv":
             kc, db = a, b
@@ -645,6 +645,10 @@ class Gen(Emitter):
         if "nolds" in self.exp:      # timing experiment: the fragments are never read; keep them finite
             for r in range(4 * self.NF):
                 e("v_mov_b32 v%d, 0" % (self.FR + r))
+        if "ldsonce" in self.exp:    # timing experiment: the fragment buffers are filled once, from K(0), and never again
+            for buf in range(self.NF):
+                e("ds_read_b128 %s, %s" % (self.vr(self.FR + 4 * buf, 4), self.vr(self.KOFF + buf % self.KS)))
+            e("s_waitcnt lgkmcnt(0)")
         self.body(0, "first")
         for b in range(4):
             self.body(b)
