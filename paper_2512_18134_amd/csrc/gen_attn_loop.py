@@ -69,8 +69,10 @@ are re-checked on the emitted text by asm_emit.check_stream in the tests):
   * scalar write of m0 -> direct load needs 1 wait state: an s_nop goes between
     them.
 
-usage: gen_attn_loop.py <config> <out.inc> [bf16|f16] [--pfd N] [--nf N] [--w N] [--dep N] [--drop part,part]
-(--pfd, --nf, --w, --dep and --drop exist for timing experiments; a library build passes none)
+usage: gen_attn_loop.py <config> <out.inc> [bf16|f16] [--pfd N] [--nf N] [--w N] [--dep N] [--ls N] [--drop part,part]
+(--pfd, --nf, --w, --dep, --ls and --drop exist for timing experiments; a library build passes none.
+ --drop parts, results are wrong with any of them: novalu, noexp, nobar, nodma, nolds (fragments zeroed),
+ ldsonce (fragments filled once from K(0)))
 """
 import os
 import struct
