@@ -171,8 +171,31 @@ def probe_mfma(args, dev):
             flop = float(n_wg) * waves * iters * 8 * 32768
             res["%d_waves_per_simd_%s" % (waves // 4, kind)] = {"ms": ms, "tflops": flop / ms / 1e9,
                                                                "frac_of_peak": flop / ms / 1e9 / PEAK_BF16_TFLOPS}
+    # what the rate on random operands depends on: the operand pattern of consecutive MFMAs, the tile shape of
+    # the instruction, the element type (one wave per SIMD; attn_probe_mfma_pattern of the debug build)
+    lib.attn_probe_mfma_pattern.restype = ctypes.c_int
+    lib.attn_probe_mfma_pattern.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    out = torch.empty((n_wg * 4 * 64,), dtype=torch.float32, device=dev)
+    rnd = torch.randn((8 * 64 * 8,), generator=gen, device=dev, dtype=torch.float32)
+    patterns = {}
+    for pattern, name in enumerate(("both_operands_change", "a_shared_by_pairs", "a_fixed_b_changes", "both_fixed",
+                                    "16x16x32_both_change", "f16_both_change")):
+        ops = rnd.to(torch.float16 if pattern == 5 else torch.bfloat16)
+        call = lambda: lib.attn_probe_mfma_pattern(ops.data_ptr(), out.data_ptr(), n_wg, pattern, iters, stream.cuda_stream)
+        for _ in range(3):
+            assert call() == 0
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for e0, e1 in evs:
+            e0.record(stream)
+            call()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+        flop = float(n_wg) * 4 * iters * 8 * 32768
+        patterns[name] = {"ms": ms, "tflops": flop / ms / 1e9, "frac_of_peak": flop / ms / 1e9 / PEAK_BF16_TFLOPS}
     print(json.dumps({"probe": "v_mfma_f32_32x32x16_bf16 issue ceiling (registers only)", "n_wg": n_wg,
-                      "iters": iters, "results": res}), flush=True)
+                      "iters": iters, "results": res, "random_operand_patterns": patterns}), flush=True)
 
 
 def probe_dq_atomics(args, dev):

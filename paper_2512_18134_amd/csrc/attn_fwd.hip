@@ -362,6 +362,30 @@ extern "C" int attn_probe_mfma(const void *operands, float *out, int n_wg, int w
 #endif
 
 #ifdef ATTN_DEBUG_ENTRY_POINTS
+// Measurement entry point of the debug build: attn_probe_mfma with four waves per workgroup and the operand
+// pattern of attn_probe_mfma_pattern_kernel (0 .. 5; 5 reads `operands` as IEEE binary16).  Patterns 0-3 and 5
+// issue iters x 8 MFMAs of 32768 FLOP per wave, pattern 4 iters x 16 of 16384 FLOP.
+extern "C" int attn_probe_mfma_pattern(const void *operands, float *out, int n_wg, int pattern, int iters, void *stream)
+{
+    if (!operands || !out)
+        return ATTN_ERR_NULL;
+    if (n_wg < 1 || iters < 1 || pattern < 0 || pattern > 5)
+        return ATTN_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const attn::bf16x8 *ops = static_cast<const attn::bf16x8 *>(operands);
+    switch (pattern) {
+    case 0: hipLaunchKernelGGL(attn::attn_probe_mfma_pattern_kernel<0>, dim3(n_wg), dim3(256), 0, st, ops, out, iters); break;
+    case 1: hipLaunchKernelGGL(attn::attn_probe_mfma_pattern_kernel<1>, dim3(n_wg), dim3(256), 0, st, ops, out, iters); break;
+    case 2: hipLaunchKernelGGL(attn::attn_probe_mfma_pattern_kernel<2>, dim3(n_wg), dim3(256), 0, st, ops, out, iters); break;
+    case 3: hipLaunchKernelGGL(attn::attn_probe_mfma_pattern_kernel<3>, dim3(n_wg), dim3(256), 0, st, ops, out, iters); break;
+    case 4: hipLaunchKernelGGL(attn::attn_probe_mfma_pattern_kernel<4>, dim3(n_wg), dim3(256), 0, st, ops, out, iters); break;
+    default: hipLaunchKernelGGL(attn::attn_probe_mfma_pattern_kernel<5>, dim3(n_wg), dim3(256), 0, st, ops, out, iters); break;
+    }
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+#endif
+
+#ifdef ATTN_DEBUG_ENTRY_POINTS
 // Measurement entry point of the debug build: the atomic traffic of a single-pass backward's dQ reduction for
 // n_heads heads of S_q queries and S_kv keys (D = 128; S_q a multiple of 64, S_kv of 128) into dq (device,
 // n_heads * S_q * 128 floats, zeroed by the caller).

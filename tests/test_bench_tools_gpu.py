@@ -52,6 +52,19 @@ def test_timeline_accounts_for_every_tile():
     assert len(d["last_end_per_xcd_us_mean_min_max"]) == 8
 
 
+def test_mfma_probe_reports_the_ceiling_and_what_it_depends_on():
+    d = run_bench("--probe-mfma", "--steps", "3")
+    res, pat = d["results"], d["random_operand_patterns"]
+    assert set(res) == {"%d_waves_per_simd_%s" % (w, k) for w in (1, 2) for k in ("random", "constant", "zero")}
+    assert set(pat) == {"both_operands_change", "a_shared_by_pairs", "a_fixed_b_changes", "both_fixed",
+                        "16x16x32_both_change", "f16_both_change"}
+    for v in list(res.values()) + list(pat.values()):
+        assert 0.3 < v["frac_of_peak"] < 1.02, v
+    # operands that are all zero cost the matrix pipe no power: nothing runs faster than that
+    assert res["1_waves_per_simd_zero"]["frac_of_peak"] > 0.9
+    assert all(v["frac_of_peak"] <= res["1_waves_per_simd_zero"]["frac_of_peak"] + 0.02 for v in pat.values())
+
+
 def test_more_than_one_gpu_is_refused():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
                          stderr=subprocess.PIPE, text=True, timeout=120)
