@@ -306,3 +306,83 @@ def walk(lines, take=(), loop_label=None, loop_visits=2, limit=200000):
         out.append(l)
         pc += 1
     return out
+
+
+def run_scalar(lines, sgprs, bn, tb, bases, limit=2000000):
+    """Execute the scalar control flow of `lines` (labels, s_mov / s_add / s_addc / s_sub / s_min / s_lshl /
+    s_and / s_cmp_ge / s_cmp_lt / s_cbranch_scc0/1 / s_branch; vector instructions are skipped, branches on
+    vcc fall through) from the SGPR values in `sgprs` ({number: value}; unset registers read 0) and return the
+    events of the run in order: ("barrier",) and ("load", which, tile, lds_address), where `bases` =
+    {"k": (base register, pointer register), "v": (...)} names the scalar pairs the direct loads go through:
+    a load through a base register takes its tile from the scalar operand of the v_add_u32 that started its
+    address (rows = tile * bn + lane part), a load through a pointer register from pointer - base (tile * tb).
+    Carries into the high word of a pointer are not modelled (addc adds its immediate only)."""
+    where = {}
+    for i, l in enumerate(lines):
+        l = l.strip()
+        if l.endswith(":"):
+            where[l[:-1]] = i
+    S = dict(sgprs)
+    scc = 0
+    m0 = 0
+    vtile = {}
+    events = []
+
+    def val(tok):
+        tok = tok.strip()
+        if tok == "m0":
+            return m0
+        if re.fullmatch(r"s\d+", tok):
+            return S.get(int(tok[1:]), 0)
+        return int(tok, 0)
+
+    pc = 0
+    steps = 0
+    while pc < len(lines):
+        steps += 1
+        assert steps < limit, "the scalar program does not end"
+        l = lines[pc].strip()
+        pc += 1
+        if not l or l.endswith(":"):
+            continue
+        op, _, rest = l.partition(" ")
+        ops = [x.strip() for x in rest.split(",")] if rest else []
+        if op == "s_branch":
+            pc = where[ops[0]]
+        elif op in ("s_cbranch_scc1", "s_cbranch_scc0"):
+            if scc == (1 if op.endswith("1") else 0):
+                pc = where[ops[0]]
+        elif op.startswith("s_cbranch"):
+            pass
+        elif op == "s_barrier":
+            events.append(("barrier",))
+        elif op in ("s_mov_b32", "s_add_u32", "s_add_i32", "s_addc_u32", "s_sub_i32", "s_min_i32", "s_lshl_b32",
+                    "s_and_b32"):
+            a = val(ops[1])
+            b = val(ops[2]) if len(ops) > 2 else 0
+            r = {"s_mov_b32": a, "s_add_u32": a + b, "s_add_i32": a + b, "s_addc_u32": a + b, "s_sub_i32": a - b,
+                 "s_min_i32": min(a, b), "s_lshl_b32": a << b, "s_and_b32": a & b}[op]
+            if op != "s_mov_b32":
+                scc = int(r != 0) if op in ("s_lshl_b32", "s_and_b32", "s_min_i32") else 0
+                if op == "s_min_i32":
+                    scc = int(a < b)
+            if ops[0] == "m0":
+                m0 = r
+            else:
+                S[int(ops[0][1:])] = r
+        elif op in ("s_cmp_ge_i32", "s_cmp_lt_i32"):
+            a, b = val(ops[0]), val(ops[1])
+            scc = int(a >= b) if op == "s_cmp_ge_i32" else int(a < b)
+        elif op == "v_add_u32" and re.fullmatch(r"s\d+", ops[1]):
+            vtile[ops[0]] = val(ops[1]) // bn
+        elif op.startswith("global_load_lds"):
+            reg = int(re.search(r"s\[(\d+):", ops[1]).group(1))
+            which = [w for w, pair in bases.items() if reg in pair][0]
+            base, ptr = bases[which]
+            off = re.search(r"offset:(\d+)", l)
+            lds = m0 + (int(off.group(1)) if off else 0)
+            tile = vtile[ops[0]] if reg == base else (S.get(ptr, 0) - S.get(base, 0)) // tb
+            events.append(("load", which, tile, lds))
+        elif op.startswith("s_") and op not in ("s_waitcnt", "s_nop"):
+            raise AssertionError("scalar instruction not modelled: " + l)
+    return events

@@ -174,11 +174,14 @@ class Gen(Emitter):
         self.s_kptr, self.s_vptr = 46, 48
         self.s_t2 = 50
         self.s_m0 = 51            # m0 of the surrounding code (reserved register: saved and restored here)
-        self.s_nm1 = 52           # index of the last tile
+        self.s_nm1 = 52           # index of this wave's last tile
         self.s_tload = 53         # first iteration whose K load (four tiles ahead) reaches past S_kv
         self.s_lk = 54            # LDS addresses of this wave's K loads, [stage] (load i: + i KB, an immediate)
         self.s_lv = self.s_lk + 4
-        self.s_last = self.s_lv + 4 - 1
+        self.s_wgnm1 = self.s_lv + 4      # index of the workgroup's last tile
+        self.s_t3 = self.s_wgnm1 + 1
+        self.s_last = self.s_t3
+        self.s_nw = self.s_last + 1       # input: tiles this wave has rows for (causal: fewer than the workgroup's)
         assert self.NLD <= 4      # the immediate offset of a load ends at 4095
         assert self.s_last < 100
 
@@ -452,6 +455,12 @@ class Gen(Emitter):
         if "nobar" not in self.exp:
             self.e("s_waitcnt vmcnt(%d)" % (0 if kind == "last" else 2 * self.NLD))
             self.e("s_barrier")
+        if kind == "last":
+            # a wave whose rows end before the workgroup's tiles do (causal) still owes the others its share of
+            # this iteration's loads: issued here, out of line, before its last products
+            self.e("s_cmp_lt_i32 s%d, s%d" % (self.s_j, self.s_wgnm1))
+            self.e("s_cbranch_scc1 %s" % L("OWED%d_" % b))
+            self.e("%s:" % L("OWEDRET%d_" % b))
         # ---- scalar work of the slots: K(j+4) -> K stage b in slot 0, V(j+2) -> V stage (b+2)%4 in slot 1
         # (nothing between the test above and these two branches writes SCC), pointer bumps in slot 2
         extra = {}
@@ -509,7 +518,7 @@ class Gen(Emitter):
                         lambda g, buf: self.mfma_texts(g[1:], buf, P_prev if g[0] == "a" else P_new, 0),
                         lambda g, buf: self.frag_loads(g[1:], buf, 0, vst if g[0] == "a" else b % 4),
                         self.NF, self.PFD, valu, extra, None, prefetched=lead, wait_every=self.W)
-            self.e("s_branch %s" % L("DONE_"))
+            self.e("s_branch %s" % L("AFTERLAST_"))
             return
         if kind == "first":
             self.outstanding = []
@@ -540,7 +549,7 @@ class Gen(Emitter):
             # tile)?  a tile that needs a mask?  the last tile?  (its loads: KSLOW / VSLOW)
             self.e("%s:" % L("SPECIAL%s_" % tag))
             if kind == "loop" and b == 1:
-                self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_ntiles))
+                self.e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_nw))
                 self.e("s_cbranch_scc1 %s" % L("EXIT1_"))
             self.e("s_cmp_lt_i32 s%d, s%d" % (self.s_j, self.s_jmask))
             self.e("s_cbranch_scc1 %s" % L("NOMASK%s_" % tag))
@@ -588,6 +597,11 @@ class Gen(Emitter):
             self.e("s_nop 7")
         self.e("s_branch %s" % L("SLOWRET%s_" % tag))
         if kind == "last":
+            self.e("%s:" % L("OWED%d_" % b))
+            if "nodma" not in self.exp:
+                self.dma_slow("k", b, 4)
+                self.dma_slow("v", (b + 2) % 4, 2)
+            self.e("s_branch %s" % L("OWEDRET%d_" % b))
             return
         # ---- ragged-tile loads
         self.e("%s:" % L("KSLOW%s_" % tag))
@@ -616,7 +630,45 @@ class Gen(Emitter):
         self.stream(pv, lambda g, buf: self.mfma_texts(g, buf, P_prev, 0),
                     lambda g, buf: self.frag_loads(g, buf, 0, vst), self.NF, self.PFD, {}, {}, None,
                     prefetched=lead, wait_every=self.W)
-        self.e("s_branch %s" % L("DONE_"))
+        self.e("s_branch %s" % L("STANDBY_"))
+
+    def standby(self):
+        """A wave that has no rows for the workgroup's remaining tiles (causal: its rows end before the
+        diagonal tile's keys do) keeps step with the others without computing: one barrier per remaining
+        iteration, and its share of every iteration's loads (the ring stage follows from the iteration number).
+        AFTERLAST: the last iteration's counter has not moved on; STANDBY: s_j = this wave's tile count."""
+        L, e = self.lab, self.e
+        sh = {128: 7, 256: 8, 512: 9}[self.ROWB]
+        tb = {4096: 12, 8192: 13, 16384: 14}[self.TB]
+        e("%s:" % L("AFTERLAST_"))
+        e("s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j))
+        e("%s:" % L("STANDBY_"))
+        e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_ntiles))
+        e("s_cbranch_scc1 %s" % L("DONE_"))
+        e("s_waitcnt vmcnt(%d)" % (2 * self.NLD))
+        e("s_barrier")
+        e("s_cmp_ge_i32 s%d, s%d" % (self.s_j, self.s_wgnm1))        # the workgroup's last iteration has no loads
+        e("s_cbranch_scc1 %s" % L("STANDBYNEXT_"))
+        for which, ahead in (("k", 4), ("v", 2)):
+            base = self.s_kbase if which == "k" else self.s_vbase
+            lds = self.s_ldsk if which == "k" else self.s_ldsv
+            e("s_add_i32 s%d, s%d, %d" % (self.s_t2, self.s_j, ahead))              # tile index
+            e("s_and_b32 s%d, s%d, 3" % (self.s_t3, self.s_t2 if which == "v" else self.s_j))   # ring stage
+            e("s_lshl_b32 s%d, s%d, %d" % (self.s_t3, self.s_t3, tb))
+            e("s_add_u32 s%d, s%d, s%d" % (self.s_t3, self.s_t3, lds))
+            e("s_lshl_b32 s%d, s%d, %d" % (self.s_t2, self.s_t2, {32: 5, 64: 6}[self.BN]))
+            for i in range(self.NLD):
+                t = self.DT + (0 if which == "k" else self.NLD) + i
+                e("v_add_u32 v%d, s%d, v%d" % (t, self.s_t2, self.DROW + i))
+                e("v_min_i32 v%d, s%d, v%d" % (t, self.s_skvm1, t))
+                e("v_lshlrev_b32 v%d, %d, v%d" % (t, sh, t))
+                e(("s_add_u32 m0, s%d, %d" % (self.s_t3, 1024 * i)) if i else ("s_mov_b32 m0, s%d" % self.s_t3))
+                e("v_add_u32 v%d, v%d, v%d" % (t, t, self.DCH + i))
+                e("s_nop 0")
+                e("global_load_lds_dwordx4 v%d, %s" % (t, self.sr(base, 2)))
+        e("%s:" % L("STANDBYNEXT_"))
+        e("s_add_i32 s%d, s%d, 1" % (self.s_j, self.s_j))
+        e("s_branch %s" % L("STANDBY_"))
 
     def generate(self):
         L = self.lab
@@ -629,7 +681,8 @@ class Gen(Emitter):
         e("s_mov_b32 s%d, 0x%08x" % (self.s_tau, self.tau_bits()))   # bound on a tile's row sum
         # first iteration that is not plain: min(first masked tile, first tile whose K load (4 tiles ahead)
         # reaches past S_kv, last tile)
-        e("s_sub_i32 s%d, s%d, 1" % (self.s_nm1, self.s_ntiles))
+        e("s_sub_i32 s%d, s%d, 1" % (self.s_nm1, self.s_nw))
+        e("s_sub_i32 s%d, s%d, 1" % (self.s_wgnm1, self.s_ntiles))
         e("s_sub_i32 s%d, s%d, 4" % (self.s_tload, self.s_tfull))
         e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_tload, self.s_jmask))
         e("s_min_i32 s%d, s%d, s%d" % (self.s_special, self.s_special, self.s_nm1))
@@ -662,6 +715,7 @@ class Gen(Emitter):
         for b in range(4):
             self.out_of_line(b, "last")
         self.drain(1)
+        self.standby()
         e("%s:" % L("DONE_"))
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
         self.restore_m0(self.s_m0)
@@ -699,6 +753,7 @@ class Gen(Emitter):
         ins.append('"{%s}"(v_head)' % self.sr(self.s_vbase, 2))
         ins.append('"{s%d}"(c_log2e)' % self.s_c)
         ins.append('"{s%d}"(n_tiles)' % self.s_ntiles)
+        ins.append('"{s%d}"(n_tiles_wave)' % self.s_nw)
         ins.append('"{s%d}"(j_mask)' % self.s_jmask)
         ins.append('"{s%d}"(t_full)' % self.s_tfull)
         ins.append('"{s%d}"(skv_m1)' % self.s_skvm1)

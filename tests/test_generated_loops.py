@@ -63,8 +63,8 @@ def test_forward_out_of_line_sections(name, b):
         assert sum(1 for l in path if l.startswith("v_mfma")) == g.NQKG * g.QB + 11 * g.NM
     # the last iteration (with and without the mask pre-pass and the exact-maximum pass) ends the loop:
     # P V of the tile before, then P V of the last tile
-    for detour in (["SPECIAL%d_" % b, "TOPL%d_" % b], ["SPECIAL%d_" % b, "NOMASK%d_" % b, "TOPL%d_" % b],
-                   ["SPECIAL%d_" % b, "TOPL%d_" % b, "SLOWL%d_" % b]):
+    for detour in (["SPECIAL%d_" % b, "TOPL%d_" % b, "DONE_"], ["SPECIAL%d_" % b, "NOMASK%d_" % b, "TOPL%d_" % b, "DONE_"],
+                   ["SPECIAL%d_" % b, "TOPL%d_" % b, "SLOWL%d_" % b, "DONE_"]):
         path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=2)
         assert asm_emit.check_stream(path) == len(path)
         assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
@@ -81,7 +81,7 @@ def test_forward_first_iteration_and_single_tile(name):
         path = asm_emit.walk(lines, take=detour, loop_label="BODY0_", loop_visits=1)
         assert asm_emit.check_stream(path) == len(path)
     # a launch with one tile: the first iteration (its loads clamped), then straight to P(0) V(0)
-    path = asm_emit.walk(lines, take=["SPECIALF_", "SLOWF_"] + clamped_loads(g, "F") + ["SPECIAL1_", "EXIT1_"])
+    path = asm_emit.walk(lines, take=["SPECIALF_", "SLOWF_"] + clamped_loads(g, "F") + ["SPECIAL1_", "EXIT1_", "DONE_"])
     assert asm_emit.check_stream(path) == len(path)
     assert sum(1 for l in path if l.startswith("v_mfma")) == (g.NQKG + g.NPVG) * g.QB
     assert path[-1].startswith("s_nop") and any(l.startswith("s_mov_b32 m0, s") for l in path[-4:])
@@ -114,6 +114,66 @@ def test_forward_load_slots_see_the_flag_the_iteration_started_with(name):
         assert sum(l.startswith("global_load_lds") for l in path[before:after]) == 2 * g.NLD
         ret = lines.index("s_branch KRET%s_" % tag, slow)
         assert lines[ret - 1].startswith("s_cmp_ge_i32 s%d, s%d" % (g.s_j, g.s_tload))
+
+
+def scalar_run(g, lines, n, n_wave, t_full, j_mask):
+    """Barriers and direct loads of one wave's run through the loop, by barrier interval."""
+    sg = {g.s_ntiles: n, g.s_nw: n_wave, g.s_tfull: t_full, g.s_jmask: j_mask, g.s_skvm1: max(t_full, 1) * g.BN - 1,
+          g.s_ldsk: 1 << 20, g.s_ldsv: 1 << 21, g.s_kbase: 0, g.s_vbase: 0}
+    ev = asm_emit.run_scalar(lines, sg, g.BN, g.TB, {"k": (g.s_kbase, g.s_kptr), "v": (g.s_vbase, g.s_vptr)})
+    intervals = []
+    for e in ev:
+        if e[0] == "barrier":
+            intervals.append([])
+        else:
+            assert intervals, "a load before the first barrier"
+            intervals[-1].append(e[1:])
+    return intervals
+
+
+@pytest.mark.parametrize("name", list(gen_attn_loop.CONFIGS))
+def test_forward_wave_without_rows_for_the_last_tiles_keeps_step(name):
+    """Causal launches: a wave whose rows end before the workgroup's tiles do stops computing after its own
+    last tile.  Whatever its tile count, it meets the same number of barriers as a wave that computes every
+    tile (one per tile: anything else hangs the workgroup), and between the same two barriers it issues the
+    same direct loads (tensor, tile, ring stage), so that the other waves find their operands."""
+    g = gen_attn_loop.Gen(name)
+    g.generate()
+    lines = [l.replace("%=", "") for l in g.lines]
+    for n in (1, 2, 3, 4, 5, 6, 7, 9, 13):
+        for t_full in (n, n - 1):
+            for j_mask in sorted({0, n // 2, n - 1, n}):
+                full = scalar_run(g, lines, n, n, t_full, j_mask)
+                assert len(full) == n
+                for j, loads in enumerate(full):     # iteration j brings K(j+4) and V(j+2), the last one nothing
+                    want = [("k", j + 4, j % 4)] * g.NLD + [("v", j + 2, (j + 2) % 4)] * g.NLD
+                    if j == n - 1 and n > 1:         # (the first iteration is not specialised: it always loads)
+                        want = []
+                    got = sorted((w, t, ((a - ((1 << 20) if w == "k" else (1 << 21))) // g.TB)) for w, t, a in loads)
+                    assert got == sorted(want), (n, t_full, j_mask, j)
+                for n_wave in range(1, n):
+                    part = scalar_run(g, lines, n, n_wave, t_full, j_mask)
+                    assert len(part) == n, (n, n_wave, t_full, j_mask)
+                    assert [sorted(x) for x in part] == [sorted(x) for x in full], (n, n_wave, t_full, j_mask)
+
+
+@pytest.mark.parametrize("name", list(gen_attn_loop.CONFIGS))
+def test_forward_early_finish_sections_obey_the_hazard_rules(name):
+    lines = fwd_lines(name)
+    g = gen_attn_loop.Gen(name)
+    for b in range(4):
+        # the wave's last tile in ring phase b and its owed loads, then three iterations of standing by: two
+        # with loads, one without
+        path = asm_emit.walk(lines, take=["SPECIAL%d_" % b, "TOPL%d_" % b, "OWED%d_" % b, "STANDBYNEXT_"],
+                             loop_label="STANDBY_", loop_visits=3)
+        assert asm_emit.check_stream(path) == len(path)
+        tail = path[[i for i, l in enumerate(path) if l.startswith("s_branch AFTERLAST_")][0]:]
+        assert sum(l == "s_barrier" for l in tail) == 3
+        assert sum(l.startswith("global_load_lds") for l in tail) == 2 * 2 * g.NLD
+    # a wave with rows for the first tile only
+    path = asm_emit.walk(lines, take=["SPECIALF_"] + clamped_loads(g, "F") + ["SPECIAL1_", "EXIT1_"],
+                         loop_label="STANDBY_", loop_visits=2)
+    assert asm_emit.check_stream(path) == len(path)
 
 
 BWD = [(ko, d, dt) for ko in (True, False) for d in (64, 128) for dt in ("bf16", "f16")]
